@@ -1,0 +1,224 @@
+"""CPU oracle for locality-constrained block-sparse attention -- TEST INFRASTRUCTURE.
+
+Thin ctypes wrappers over ``lcsa_oracle.c`` (fp64, plain loops) plus a
+list-based model of the sliding-window KV cache.  Only tests, the smoke check
+and the benchmark's ``cpu_baseline`` leg may import this package; it shares no
+code with the HIP library and never calls it.
+
+Paper passages followed: Sec. 3.2 "Stage 2" (blocks, pooling, coarse map,
+top-k, full attention on kept pairs), Sec. 3.3 / Fig. 3 (local window),
+eq. (1) (softmax with 1/sqrt(d)), appendix "Discussion on Stream VSR
+Pipelines" (sliding-window cache of recent latents + current chunk).
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from dataclasses import dataclass
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "lcsa_oracle.c")
+_LIB_PATH = os.path.join(_HERE, "liblcsa_oracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile lcsa_oracle.c with gcc (OpenMP, -O2, no fast-math)."""
+    stale = (not os.path.exists(_LIB_PATH)
+             or os.path.getmtime(_LIB_PATH) < os.path.getmtime(_SRC))
+    if force or stale:
+        subprocess.run(["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c99",
+                        "-o", _LIB_PATH, _SRC, "-lm"], check=True)
+    return _LIB_PATH
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        _lib = ctypes.CDLL(_LIB_PATH)
+        _lib.lcsa_oracle_blocks_per_frame.restype = ctypes.c_int
+        _lib.lcsa_oracle_allowed.restype = ctypes.c_int
+        _lib.lcsa_oracle_threads.restype = ctypes.c_int
+    return _lib
+
+
+def _p(a, ty):
+    return a.ctypes.data_as(ctypes.POINTER(ty))
+
+
+_f32, _f64, _i32 = ctypes.c_float, ctypes.c_double, ctypes.c_int32
+_ci, _cl = ctypes.c_int, ctypes.c_int64
+
+
+@dataclass(frozen=True)
+class Geometry:
+    """Problem geometry in the paper's terms (one block = one th x tw tile of one frame)."""
+    heads: int
+    head_dim: int
+    grid_h: int
+    grid_w: int
+    tile_h: int
+    tile_w: int
+    q_frames: int
+    radius_h: int      # tokens between block centres; < 0: unbounded
+    radius_w: int
+    topk: int
+    window_mode: int = 0   # 0 boundary-truncated, 1 boundary-preserved
+
+    @property
+    def nb(self) -> int:
+        return _load().lcsa_oracle_blocks_per_frame(self.grid_h, self.grid_w, self.tile_h, self.tile_w)
+
+    @property
+    def tokens_per_frame(self) -> int:
+        return self.grid_h * self.grid_w
+
+
+def threads() -> int:
+    return _load().lcsa_oracle_threads()
+
+
+def _tokens_view(x: np.ndarray):
+    """x: float32 [tokens][heads][d] (any token/head strides, d contiguous)."""
+    assert x.dtype == np.float32 and x.ndim == 3 and x.strides[2] == 4
+    return x, x.strides[0] // 4, x.strides[1] // 4
+
+
+def pool(x: np.ndarray, g: Geometry, n_frames: int) -> np.ndarray:
+    """Block means of x -> float64 [heads][n_frames*nb][d]  (Sec. 3.2)."""
+    x, st, sh = _tokens_view(x)
+    assert x.shape == (n_frames * g.tokens_per_frame, g.heads, g.head_dim)
+    out = np.empty((g.heads, n_frames * g.nb, g.head_dim), np.float64)
+    _load().lcsa_oracle_pool(_p(x, _f32), _cl(st), _cl(sh), _ci(g.heads), _ci(g.head_dim),
+                             _ci(n_frames), _ci(g.grid_h), _ci(g.grid_w), _ci(g.tile_h), _ci(g.tile_w),
+                             _p(out, _f64))
+    return out
+
+
+def scores(pooled_q: np.ndarray, pooled_k: np.ndarray) -> np.ndarray:
+    """Coarse block-to-block map S[h][qb][kb] = <q_bar, k_bar>  (Sec. 3.2)."""
+    pooled_q = np.ascontiguousarray(pooled_q, np.float64)
+    pooled_k = np.ascontiguousarray(pooled_k, np.float64)
+    h, n_qb, d = pooled_q.shape
+    n_kb = pooled_k.shape[1]
+    S = np.empty((h, n_qb, n_kb), np.float64)
+    _load().lcsa_oracle_scores(_p(pooled_q, _f64), _p(pooled_k, _f64), _ci(h), _ci(n_qb), _ci(n_kb), _ci(d),
+                               _p(S, _f64))
+    return S
+
+
+def allowed(qb: int, kb: int, g: Geometry) -> bool:
+    """Spatial local-window predicate on block ids (Sec. 3.3, Fig. 3)."""
+    return bool(_load().lcsa_oracle_allowed(_ci(qb), _ci(kb), _ci(g.grid_h), _ci(g.grid_w), _ci(g.tile_h),
+                                            _ci(g.tile_w), _ci(g.radius_h), _ci(g.radius_w), _ci(g.window_mode)))
+
+
+def select(S: np.ndarray, g: Geometry, kv_frames: int):
+    """Top-k admissible key blocks per (head, query block): (sel_idx, sel_cnt, gap)."""
+    S = np.ascontiguousarray(S, np.float64)
+    n_qb, n_kb = g.q_frames * g.nb, kv_frames * g.nb
+    assert S.shape == (g.heads, n_qb, n_kb)
+    sel_idx = np.empty((g.heads, n_qb, g.topk), np.int32)
+    sel_cnt = np.empty((g.heads, n_qb), np.int32)
+    gap = np.empty((g.heads, n_qb), np.float64)
+    _load().lcsa_oracle_select(_p(S, _f64), _ci(g.heads), _ci(g.q_frames), _ci(kv_frames),
+                               _ci(g.grid_h), _ci(g.grid_w), _ci(g.tile_h), _ci(g.tile_w),
+                               _ci(g.radius_h), _ci(g.radius_w), _ci(g.window_mode), _ci(g.topk),
+                               _p(sel_idx, _i32), _p(sel_cnt, _i32), _p(gap, _f64))
+    return sel_idx, sel_cnt, gap
+
+
+def attend(q: np.ndarray, k: np.ndarray, v: np.ndarray, g: Geometry, kv_frames: int,
+           sel_idx: np.ndarray, sel_cnt: np.ndarray, scale: float = 0.0, rows=None,
+           with_lse: bool = False):
+    """Exact softmax attention over the kept blocks (Sec. 3.2, eq. 1).
+
+    q: [q_frames*H*W][heads][d] float32; k, v: [kv_frames*H*W][heads][d] float32
+    (oldest visible frame first, the chunk's own frames last).  rows: optional
+    int array [[head, qb], ...] restricting the work to those query blocks
+    (other entries of the result are NaN).  Returns o float64 [tokens][heads][d]
+    (and lse [tokens][heads] if asked).
+    """
+    q, qst, qsh = _tokens_view(q)
+    k, kst, ksh = _tokens_view(k)
+    v, vst, vsh = _tokens_view(v)
+    assert (kst, ksh) == (vst, vsh) and k.shape == v.shape
+    assert q.shape == (g.q_frames * g.tokens_per_frame, g.heads, g.head_dim)
+    assert k.shape == (kv_frames * g.tokens_per_frame, g.heads, g.head_dim)
+    sel_idx = np.ascontiguousarray(sel_idx, np.int32)
+    sel_cnt = np.ascontiguousarray(sel_cnt, np.int32)
+    topk = sel_idx.shape[-1]
+    assert sel_idx.shape == (g.heads, g.q_frames * g.nb, topk)
+    o = np.full((q.shape[0], g.heads, g.head_dim), np.nan, np.float64)
+    lse = np.full((q.shape[0], g.heads), np.nan, np.float64) if with_lse else None
+    if rows is None:
+        rows_p, n_rows = None, -1
+    else:
+        rows = np.ascontiguousarray(rows, np.int32).reshape(-1, 2)
+        rows_p, n_rows = _p(rows, _i32), rows.shape[0]
+    _load().lcsa_oracle_attend(_p(q, _f32), _cl(qst), _cl(qsh), _p(k, _f32), _p(v, _f32), _cl(kst), _cl(ksh),
+                               _ci(g.heads), _ci(g.head_dim), _ci(g.q_frames), _ci(kv_frames),
+                               _ci(g.grid_h), _ci(g.grid_w), _ci(g.tile_h), _ci(g.tile_w),
+                               _p(sel_idx, _i32), _p(sel_cnt, _i32), _ci(topk), _f64(scale),
+                               rows_p, _ci(n_rows), _p(o, _f64), _p(lse, _f64) if with_lse else None)
+    return (o, lse) if with_lse else o
+
+
+def attend_weights(q, k, v, g: Geometry, kv_frames: int, blocks, head: int, q_tok: int, scale: float = 0.0):
+    """Softmax weights of one query token over ALL key tokens (zero outside `blocks`) and its output."""
+    q, qst, qsh = _tokens_view(q)
+    k, kst, ksh = _tokens_view(k)
+    v, vst, vsh = _tokens_view(v)
+    blocks = np.ascontiguousarray(blocks, np.int32)
+    w = np.zeros(kv_frames * g.tokens_per_frame, np.float64)
+    o = np.empty(g.head_dim, np.float64)
+    _load().lcsa_oracle_attend_weights(_p(q, _f32), _cl(qst), _cl(qsh), _p(k, _f32), _p(v, _f32), _cl(kst), _cl(ksh),
+                                       _ci(g.head_dim), _ci(kv_frames), _ci(g.grid_h), _ci(g.grid_w),
+                                       _ci(g.tile_h), _ci(g.tile_w), _p(blocks, _i32), _ci(len(blocks)),
+                                       _f64(scale), _ci(head), _cl(q_tok), _p(o, _f64), _p(w, _f64))
+    return w, o
+
+
+class SlidingWindowCache:
+    """KV cache with sliding-window eviction as a plain list of frames
+    (appendix "Discussion on Stream VSR Pipelines"; KV-cache eviction appendix:
+    sliding window is the default).  Capacity counts the current chunk's frames."""
+
+    def __init__(self, capacity_frames: int):
+        self.capacity = capacity_frames
+        self.k_frames: list[np.ndarray] = []
+        self.v_frames: list[np.ndarray] = []
+
+    def append(self, k: np.ndarray, v: np.ndarray, n_frames: int) -> None:
+        """k, v: [n_frames*H*W][heads][d]; newest frames go to the back, oldest fall off the front."""
+        per = k.shape[0] // n_frames
+        for f in range(n_frames):
+            self.k_frames.append(np.array(k[f * per:(f + 1) * per]))
+            self.v_frames.append(np.array(v[f * per:(f + 1) * per]))
+        while len(self.k_frames) > self.capacity:
+            self.k_frames.pop(0)
+            self.v_frames.pop(0)
+
+    @property
+    def valid_frames(self) -> int:
+        return len(self.k_frames)
+
+    def visible(self):
+        """(K, V) of every visible frame, oldest first: [valid_frames*H*W][heads][d]."""
+        return np.concatenate(self.k_frames, 0), np.concatenate(self.v_frames, 0)
+
+
+def lcsa(q: np.ndarray, k: np.ndarray, v: np.ndarray, g: Geometry, kv_frames: int, rows=None):
+    """The whole path on visible K/V: pool -> coarse map -> window + top-k -> attend.
+
+    Returns dict(pooled_q, pooled_k, S, sel_idx, sel_cnt, gap, o)."""
+    pq = pool(q, g, g.q_frames)
+    pk = pool(k, g, kv_frames)
+    S = scores(pq, pk)
+    sel_idx, sel_cnt, gap = select(S, g, kv_frames)
+    o = attend(q, k, v, g, kv_frames, sel_idx, sel_cnt, rows=rows)
+    return dict(pooled_q=pq, pooled_k=pk, S=S, sel_idx=sel_idx, sel_cnt=sel_cnt, gap=gap, o=o)

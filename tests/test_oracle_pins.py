@@ -1,0 +1,359 @@
+"""Pins for the CPU oracle: each test ties one part of oracle/ to something the
+paper or plain mathematics fixes, independent of the oracle's own code.
+
+The paper prints no worked numeric example of the attention, so agreement with
+the authors' implementation is unpinned; what is pinned is the definition.
+"""
+import os
+
+import numpy as np
+import pytest
+from scipy.special import logsumexp, softmax
+
+import oracle
+from oracle import Geometry
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+
+
+def rand_qkv(rng, g, kv_frames):
+    n = g.grid_h * g.grid_w
+    q = rng.standard_normal((g.q_frames * n, g.heads, g.head_dim)).astype(np.float32)
+    k = rng.standard_normal((kv_frames * n, g.heads, g.head_dim)).astype(np.float32)
+    v = rng.standard_normal((kv_frames * n, g.heads, g.head_dim)).astype(np.float32)
+    return q, k, v
+
+
+def dense_attention(q, k, v, mask=None):
+    """Textbook softmax(QK^T/sqrt(d))V per head via library routines; mask[tq][tk] bool."""
+    d = q.shape[-1]
+    logits = np.einsum("ihc,jhc->hij", q.astype(np.float64), k.astype(np.float64)) / np.sqrt(d)
+    if mask is not None:
+        logits = np.where(mask[None], logits, -np.inf)
+    p = softmax(logits, axis=-1)
+    return np.einsum("hij,jhc->ihc", p, v.astype(np.float64)), logsumexp(logits, axis=-1).T
+
+
+TINY = Geometry(heads=1, head_dim=32, grid_h=6, grid_w=8, tile_h=4, tile_w=4, q_frames=2,
+                radius_h=4, radius_w=4, topk=4)
+
+
+# ---- P1: k = all blocks and unbounded window  ==  dense softmax attention (Sec. 3.2, eq. 1)
+@pytest.mark.parametrize("geom,kv_frames", [
+    (Geometry(1, 32, 6, 8, 4, 4, 2, -1, -1, 16), 4),        # Tiny grid: half tiles on the bottom row
+    (Geometry(3, 8, 5, 7, 2, 3, 1, -1, -1, 3 * 3 * 3), 3),  # ragged in both axes, several heads
+    (Geometry(2, 16, 4, 4, 4, 4, 2, -1, -1, 5), 5),         # one tile per frame
+])
+def test_reduces_to_dense_attention(geom, kv_frames):
+    rng = np.random.default_rng(1)
+    q, k, v = rand_qkv(rng, geom, kv_frames)
+    res = oracle.lcsa(q, k, v, geom, kv_frames)
+    assert (res["sel_cnt"] == kv_frames * geom.nb).all()
+    want, want_lse = dense_attention(q, k, v)
+    np.testing.assert_allclose(res["o"], want, rtol=0, atol=1e-12)
+    _, lse = oracle.attend(q, k, v, geom, kv_frames, res["sel_idx"], res["sel_cnt"], with_lse=True)
+    np.testing.assert_allclose(lse, want_lse, rtol=0, atol=1e-12)
+
+
+def test_dense_with_strided_head_major_inputs():
+    """[heads][tokens][d] storage viewed as [tokens][heads][d] must give the same answer."""
+    g = Geometry(2, 8, 4, 6, 2, 3, 1, -1, -1, 8)
+    rng = np.random.default_rng(2)
+    q, k, v = rand_qkv(rng, g, 2)
+    qh, kh, vh = (np.ascontiguousarray(x.transpose(1, 0, 2)).transpose(1, 0, 2) for x in (q, k, v))
+    a = oracle.lcsa(q, k, v, g, 2)["o"]
+    b = oracle.lcsa(qh, kh, vh, g, 2)["o"]
+    np.testing.assert_array_equal(a, b)
+
+
+# ---- P10: hand-enumerated window sets (Sec. 3.3, Fig. 3)
+def load_window_sets():
+    out = []
+    for line in open(os.path.join(HERE, "golden", "window_sets.txt")):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        head, tiles = line.split(":")
+        mode, qt = head.split()
+        out.append((mode, int(qt), sorted(int(t) for t in tiles.split())))
+    return out
+
+
+@pytest.mark.parametrize("mode,qt,tiles", load_window_sets())
+def test_window_sets_match_hand_enumeration(mode, qt, tiles):
+    g = Geometry(1, 4, 12, 16, 4, 4, 2, 4, 4, 1, window_mode={"truncated": 0, "preserved": 1}[mode])
+    nb = g.nb
+    assert nb == 12
+    for qf in range(2):
+        for kf in range(3):          # frames play no role
+            got = [kt for kt in range(nb) if oracle.allowed(qf * nb + qt, kf * nb + kt, g)]
+            assert got == tiles
+
+
+def test_window_radius_boundaries():
+    """Centre distance is a multiple of the tile size: radius 7 -> +-1 tile, 8 -> +-2 (tile 4);
+    radius 0 -> same tile position only; odd tile sizes; per-axis radii."""
+    def row_reach(radius, tile, n=9, q=4):
+        g = Geometry(1, 4, tile * n, 5, tile, 5, 1, radius, -1, 1)
+        return [b for b in range(n) if oracle.allowed(q, b, g)]
+    assert row_reach(7, 4) == [3, 4, 5]
+    assert row_reach(8, 4) == [2, 3, 4, 5, 6]
+    assert row_reach(3, 4) == [4]
+    assert row_reach(0, 4) == [4]
+    assert row_reach(5, 5) == [3, 4, 5]
+    assert row_reach(9, 3) == [1, 2, 3, 4, 5, 6, 7]
+    # per-axis: rows unbounded, columns radius 0
+    g = Geometry(1, 4, 8, 12, 4, 4, 1, -1, 0, 1)
+    assert [b for b in range(6) if oracle.allowed(1, b, g)] == [1, 4]
+    # the paper-scale window: 8x16 tiles, radius 24 -> +-3 tile rows, +-1 tile column
+    g = Geometry(1, 4, 48, 88, 8, 16, 1, 24, 24, 1)
+    got = [b for b in range(36) if oracle.allowed(3 * 6 + 2, b, g)]
+    assert got == [r * 6 + c for r in range(6) for c in (1, 2, 3)]
+    # partial edge tiles use the nominal (unclipped) centre: last column (8 of 16 tokens wide)
+    got = [b for b in range(36) if oracle.allowed(0 * 6 + 5, b, g)]
+    assert got == [r * 6 + c for r in range(4) for c in (4, 5)]
+
+
+# ---- P2: k >= n_allowed with a finite window == windowed dense attention
+@pytest.mark.parametrize("mode", [0, 1])
+def test_windowed_dense_attention(mode):
+    g = Geometry(2, 8, 12, 16, 4, 4, 2, 4, 4, 27, window_mode=mode)
+    kv_frames = 3
+    rng = np.random.default_rng(3)
+    q, k, v = rand_qkv(rng, g, kv_frames)
+    sets = {(m, qt): t for m, qt, t in load_window_sets()}
+    name = "truncated" if mode == 0 else "preserved"
+    # token-level mask from the hand-written tile sets (tiles not listed in the fixture are skipped)
+    def tile_of(tok):
+        r, c = (tok % 192) // 16, tok % 16
+        return (r // 4) * 4 + c // 4
+    qt = np.array([tile_of(t) for t in range(q.shape[0])])
+    kt = np.array([tile_of(t) for t in range(k.shape[0])])
+    listed = [t for t in range(12) if (name, t) in sets]
+    mask = np.zeros((q.shape[0], k.shape[0]), bool)
+    for t in listed:
+        mask[np.ix_(qt == t, np.isin(kt, sets[(name, t)]))] = True
+    res = oracle.lcsa(q, k, v, g, kv_frames)
+    rows = np.isin(qt, listed)
+    mask[~rows] = True
+    want, _ = dense_attention(q, k, v, mask)
+    np.testing.assert_allclose(res["o"][rows], want[rows], rtol=0, atol=1e-12)
+    for t in listed:
+        for f in range(2):
+            assert res["sel_cnt"][0, f * 12 + t] == 3 * len(sets[(name, t)])
+
+
+# ---- pooling: library mean when tiles divide the grid; closed forms on ragged grids
+def test_pool_equals_reshape_mean_when_tiles_divide():
+    g = Geometry(3, 5, 8, 12, 4, 3, 2, -1, -1, 1)
+    rng = np.random.default_rng(4)
+    x = rng.standard_normal((2 * 96, 3, 5)).astype(np.float32)
+    want = x.astype(np.float64).reshape(2, 2, 4, 4, 3, 3, 5).mean(axis=(2, 4))   # f,by,bx,h,d
+    want = want.transpose(3, 0, 1, 2, 4).reshape(3, 2 * 8, 5)
+    np.testing.assert_allclose(oracle.pool(x, g, 2), want, rtol=0, atol=1e-15)
+
+
+def test_pool_partial_tiles_divide_by_valid_count():
+    """x = a*row + b*col + c*frame: the mean over a (possibly clipped) tile is x at its centroid."""
+    g = Geometry(1, 1, 6, 8, 4, 3, 2, -1, -1, 1)          # 2 x 3 tiles, bottom row 2 high, right col 2 wide
+    f, r, c = np.meshgrid(np.arange(2), np.arange(6), np.arange(8), indexing="ij")
+    x = (0.5 * r + 0.25 * c + 2.0 * f).astype(np.float32).reshape(-1, 1, 1)
+    got = oracle.pool(x, g, 2).reshape(2, 2, 3)
+    rows = [1.5, 4.5]               # centroids of rows {0..3}, {4,5}
+    cols = [1.0, 4.0, 6.5]          # centroids of cols {0..2}, {3..5}, {6,7}
+    for ff in range(2):
+        for by in range(2):
+            for bx in range(3):
+                assert got[ff, by, bx] == pytest.approx(0.5 * rows[by] + 0.25 * cols[bx] + 2.0 * ff, abs=1e-14)
+
+
+def test_scores_equal_einsum():
+    rng = np.random.default_rng(5)
+    pq, pk = rng.standard_normal((2, 7, 9)), rng.standard_normal((2, 11, 9))
+    np.testing.assert_allclose(oracle.scores(pq, pk), np.einsum("hqc,hkc->hqk", pq, pk), rtol=0, atol=1e-14)
+
+
+# ---- top-k: library sort on an unbounded window; P3 invariants under a window
+def test_topk_equals_stable_argsort_unbounded():
+    g = Geometry(2, 4, 8, 8, 4, 4, 2, -1, -1, 5)
+    kv = 3
+    rng = np.random.default_rng(6)
+    S = rng.standard_normal((2, 2 * 4, kv * 4))
+    S[0, 0, :] = np.round(S[0, 0, :])            # force exact ties on one row
+    S[1, 3, :] = 0.0                             # and an all-tie row
+    idx, cnt, gap = oracle.select(S, g, kv)
+    order = np.argsort(-S, axis=-1, kind="stable")   # stable: among equals the lower index first
+    want = np.sort(order[..., :5], axis=-1)
+    np.testing.assert_array_equal(idx, want)
+    assert (cnt == 5).all()
+    srt = -np.sort(-S, axis=-1)
+    np.testing.assert_allclose(gap, srt[..., 4] - srt[..., 5], rtol=0, atol=0)
+    assert gap[1, 3] == 0.0
+
+
+@pytest.mark.parametrize("mode", [0, 1])
+def test_selection_invariants_under_window(mode):
+    g = Geometry(2, 4, 20, 28, 4, 4, 2, 6, 9, 7, window_mode=mode)   # 5 x 7 tiles, +-1 rows, +-2 cols
+    kv = 4
+    nb = g.nb
+    rng = np.random.default_rng(7)
+    S = rng.standard_normal((2, 2 * nb, kv * nb))
+    idx, cnt, gap = oracle.select(S, g, kv)
+    for h in range(2):
+        for qb in range(2 * nb):
+            adm = [kb for kb in range(kv * nb) if oracle.allowed(qb, kb, g)]
+            m = min(7, len(adm))
+            assert cnt[h, qb] == m
+            kept = idx[h, qb, :m]
+            assert (idx[h, qb, m:] == -1).all()
+            assert (np.diff(kept) > 0).all()                     # ascending, unique
+            assert set(kept) <= set(adm)                         # never outside the window
+            rest = sorted(set(adm) - set(kept))
+            if rest:
+                assert S[h, qb, kept].min() >= S[h, qb, rest].max()
+                assert gap[h, qb] == pytest.approx(S[h, qb, kept].min() - S[h, qb, rest].max(), abs=0)
+            else:
+                assert np.isinf(gap[h, qb])
+
+
+def test_fewer_candidates_than_k_keeps_all_and_pads():
+    g = Geometry(1, 4, 8, 8, 4, 4, 1, 0, 0, 6)       # radius 0: only the same tile position
+    S = np.random.default_rng(8).standard_normal((1, 4, 3 * 4))
+    idx, cnt, gap = oracle.select(S, g, 3)
+    for qb in range(4):
+        assert cnt[0, qb] == 3
+        assert list(idx[0, qb]) == [qb, 4 + qb, 8 + qb, -1, -1, -1]
+        assert np.isinf(gap[0, qb])
+
+
+# ---- P5: Q = 0 -> pure tie-break, and uniform weights over the kept blocks' valid tokens
+def test_zero_queries_closed_form():
+    g = Geometry(2, 8, 6, 8, 4, 4, 2, 4, 100, 3)      # 2 x 2 tiles/frame; bottom tiles are 2 rows high
+    kv = 3
+    rng = np.random.default_rng(9)
+    q, k, v = rand_qkv(rng, g, kv)
+    q[:] = 0.0
+    res = oracle.lcsa(q, k, v, g, kv)
+    assert (res["sel_idx"] == np.array([0, 1, 2])).all()      # lowest ids: tiles 0,1,2 of the oldest frame
+    toks = [r * 8 + c for r in range(4) for c in range(8)] + [r * 8 + c for r in (4, 5) for c in range(4)]
+    want = v[toks].astype(np.float64).mean(axis=0)              # [heads][d]
+    np.testing.assert_allclose(res["o"], np.broadcast_to(want, res["o"].shape), rtol=0, atol=1e-14)
+
+
+# ---- P6 / P4: constant V, convexity, weights
+def test_constant_v_and_convexity():
+    g = TINY
+    kv = 4
+    rng = np.random.default_rng(10)
+    q, k, v = rand_qkv(rng, g, kv)
+    res = oracle.lcsa(q, k, v, g, kv)
+    vc = np.full_like(v, 0.375)
+    o = oracle.attend(q, k, vc, g, kv, res["sel_idx"], res["sel_cnt"])
+    np.testing.assert_allclose(o, 0.375, rtol=0, atol=1e-15)
+    nb, n = g.nb, g.grid_h * g.grid_w
+    for tok in (0, 17, 47, 48 + 40, 95):
+        f, r, c = tok // n, (tok % n) // 8, tok % 8
+        qb = f * nb + (r // 4) * 2 + c // 4
+        blocks = res["sel_idx"][0, qb, :res["sel_cnt"][0, qb]]
+        w, o1 = oracle.attend_weights(q, k, v, g, kv, blocks, 0, tok)
+        assert w.min() >= 0 and w.sum() == pytest.approx(1.0, abs=1e-14)
+        # support = exactly the tokens of the kept blocks
+        tiles = np.array([(t // n) * nb + (((t % n) // 8) // 4) * 2 + (t % 8) // 4 for t in range(kv * n)])
+        assert ((w > 0) == np.isin(tiles, blocks)).all()
+        np.testing.assert_allclose(o1, res["o"][tok, 0], rtol=0, atol=1e-15)
+        np.testing.assert_allclose(o1, w @ v[:, 0, :].astype(np.float64), rtol=0, atol=1e-14)
+        sup = v[w > 0, 0, :]
+        assert (o1 <= sup.max(0) + 1e-15).all() and (o1 >= sup.min(0) - 1e-15).all()
+
+
+# ---- P7: adding the same vector to every key changes neither selection nor output...
+def test_key_shift_invariance_of_attention():
+    """...for the exact attention stage (each query's logits all move by the same amount)."""
+    g = Geometry(2, 8, 8, 8, 4, 4, 1, 4, 4, 3)
+    kv = 2
+    rng = np.random.default_rng(11)
+    q, k, v = rand_qkv(rng, g, kv)
+    # dyadic values so the shifted keys stay exact in float32
+    k = np.round(k * 8) / 8
+    u = (np.round(rng.standard_normal((1, 2, 8)) * 4) / 4).astype(np.float32)
+    res = oracle.lcsa(q, k, v, g, kv)
+    o2 = oracle.attend(q, k + u, v, g, kv, res["sel_idx"], res["sel_cnt"])
+    np.testing.assert_allclose(o2, res["o"], rtol=0, atol=1e-13)
+    # the pooled map moves by a per-row constant, so the selection is unchanged too
+    res2 = oracle.lcsa(q, k + u, v, g, kv)
+    np.testing.assert_array_equal(res2["sel_idx"], res["sel_idx"])
+
+
+# ---- P8: a frame duplicated bit for bit ties exactly; the older copy wins
+def test_duplicate_frame_tie_prefers_older():
+    g = Geometry(1, 8, 8, 8, 4, 4, 1, -1, -1, 2)
+    rng = np.random.default_rng(12)
+    n = 64
+    q = rng.standard_normal((n, 1, 8)).astype(np.float32)
+    kf = rng.standard_normal((n, 1, 8)).astype(np.float32)
+    k = np.concatenate([kf, kf], 0)
+    v = rng.standard_normal((2 * n, 1, 8)).astype(np.float32)
+    res = oracle.lcsa(q, k, v, g, 2)
+    S = res["S"]
+    np.testing.assert_array_equal(S[..., :4], S[..., 4:])
+    for qb in range(4):
+        best = int(np.argmax(S[0, qb, :4]))
+        assert list(res["sel_idx"][0, qb]) == [best, best + 4]   # both copies of the best tile...
+    g1 = Geometry(1, 8, 8, 8, 4, 4, 1, -1, -1, 1)
+    res1 = oracle.lcsa(q, k, v, g1, 2)
+    for qb in range(4):
+        assert res1["sel_idx"][0, qb, 0] == int(np.argmax(S[0, qb, :4]))   # ...and with k=1 the older one
+        assert res1["gap"][0, qb] == 0.0
+
+
+# ---- P9: sliding-window cache == the last C frames of the full history
+def test_sliding_window_cache_model():
+    cap, tq, per = 6, 2, 5
+    cache = oracle.SlidingWindowCache(cap)
+    hist_k, hist_v = [], []
+    rng = np.random.default_rng(13)
+    for chunk in range(7):
+        k = rng.standard_normal((tq * per, 1, 2)).astype(np.float32)
+        v = rng.standard_normal((tq * per, 1, 2)).astype(np.float32)
+        cache.append(k, v, tq)
+        hist_k.append(k)
+        hist_v.append(v)
+        allk, allv = np.concatenate(hist_k), np.concatenate(hist_v)
+        keep = min((chunk + 1) * tq, cap) * per
+        K, V = cache.visible()
+        assert cache.valid_frames == keep // per
+        np.testing.assert_array_equal(K, allk[-keep:])
+        np.testing.assert_array_equal(V, allv[-keep:])
+    # odd chunk size against an even capacity: a chunk may straddle the eviction point
+    cache = oracle.SlidingWindowCache(4)
+    frames = [np.full((per, 1, 2), i, np.float32) for i in range(9)]
+    for i in range(0, 9, 3):
+        x = np.concatenate(frames[i:i + 3])
+        cache.append(x, x, 3)
+    assert [int(f[0, 0, 0]) for f in cache.k_frames] == [5, 6, 7, 8]
+
+
+# ---- scale argument and density sanity
+def test_explicit_scale_matches_default_and_changes_result():
+    g = Geometry(1, 16, 4, 4, 4, 4, 1, -1, -1, 2)
+    rng = np.random.default_rng(14)
+    q, k, v = rand_qkv(rng, g, 2)
+    res = oracle.lcsa(q, k, v, g, 2)
+    a = oracle.attend(q, k, v, g, 2, res["sel_idx"], res["sel_cnt"], scale=0.25)
+    np.testing.assert_array_equal(a, res["o"])
+    b = oracle.attend(q, k, v, g, 2, res["sel_idx"], res["sel_cnt"], scale=1.0)
+    want, _ = dense_attention(q * 4.0, k, v)          # scale 1.0 == logits * sqrt(d)
+    np.testing.assert_allclose(b, want, rtol=0, atol=1e-12)
+
+
+def test_rows_argument_restricts_work():
+    g = TINY
+    rng = np.random.default_rng(15)
+    q, k, v = rand_qkv(rng, g, 4)
+    full = oracle.lcsa(q, k, v, g, 4)
+    part = oracle.attend(q, k, v, g, 4, full["sel_idx"], full["sel_cnt"], rows=[[0, 3], [0, 6]])
+    done = ~np.isnan(part[:, 0, 0])
+    # tile 3 of frame 0 = rows 4,5 x cols 4..7 ; tile 2 of frame 1 = rows 4,5 x cols 0..3
+    want = sorted([r * 8 + c for r in (4, 5) for c in range(4, 8)] + [48 + r * 8 + c for r in (4, 5) for c in range(4)])
+    assert list(np.nonzero(done)[0]) == want
+    np.testing.assert_array_equal(part[done], full["o"][done])
