@@ -1,0 +1,163 @@
+/*
+ * lcsa.h -- C ABI of the MI355X (gfx950) library for locality-constrained
+ * block-sparse spatiotemporal attention, the self-attention of FlashVSR's
+ * one-step streaming diffusion transformer (arXiv 2510.12747).
+ *
+ * One layer call for one chunk of latent frames is, in this order,
+ *     lcsa_kv_cache_append   keys/values of the chunk join the sliding-window cache
+ *     lcsa_pool_blocks       block means of the chunk's queries
+ *     lcsa_select_blocks     coarse block map, spatial window, per-row top-k
+ *     lcsa_sparse_attn_fwd   exact softmax attention on the kept block pairs
+ *
+ * General rules
+ *   - Every pointer named "device" is GPU memory owned by the caller.  The
+ *     library never allocates or frees device memory and never synchronises:
+ *     each call validates its arguments on the host, enqueues kernels on the
+ *     given stream (a hipStream_t passed as void*, NULL = default stream) and
+ *     returns.  The cache's ring position advances on the host at enqueue time,
+ *     so all calls that touch one cache must be issued in program order on one
+ *     stream.
+ *   - Tokens of a tensor are in raster order: token = (frame*grid_h + row)*grid_w + col.
+ *     Element (token, head, c) of x is x[token*stride_tok + head*stride_head + c];
+ *     strides are in elements, c is contiguous.  Base pointers must be 16-byte
+ *     aligned and strides multiples of 16 bytes.
+ *   - A block is one tile_h x tile_w tile of one frame; tiles on the right and
+ *     bottom edge of a grid the tile does not divide hold fewer (valid) tokens.
+ *     nb = ceil(grid_h/tile_h)*ceil(grid_w/tile_w) blocks per frame.  Block id =
+ *     frame*nb + tile_row*ceil(grid_w/tile_w) + tile_col.  For key blocks frame 0
+ *     is the OLDEST frame currently visible in the cache and the chunk's own
+ *     frames come last; for query blocks frame 0 is the chunk's first frame.
+ *   - Return value: LCSA_OK or a negative lcsa_status.  Nothing is enqueued
+ *     when a call fails validation.  No call aborts, throws or prints.
+ */
+#ifndef LCSA_H
+#define LCSA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum lcsa_status {
+    LCSA_OK = 0,
+    LCSA_EINVAL = -1,       /* null pointer, non-positive size, bad stride/alignment, wrong state   */
+    LCSA_EUNSUPPORTED = -2, /* valid request that no kernel of this build covers                    */
+    LCSA_EHIP = -3          /* the HIP runtime reported an error at launch                          */
+} lcsa_status;
+
+enum { LCSA_F32 = 0, LCSA_BF16 = 1 };
+enum { LCSA_WINDOW_TRUNCATED = 0, LCSA_WINDOW_PRESERVED = 1 };
+
+/* Problem geometry.  Plain data, passed by pointer, validated on every call. */
+typedef struct lcsa_geom {
+    int32_t heads;         /* attention heads                                                        */
+    int32_t head_dim;      /* d; multiple of 8 (bf16) / 4 (f32), at most 256                         */
+    int32_t grid_h;        /* latent tokens per frame: rows                                          */
+    int32_t grid_w;        /*                          columns                                       */
+    int32_t tile_h;        /* block = tile_h x tile_w tokens of one frame (Sec. 3.2)                 */
+    int32_t tile_w;
+    int32_t q_frames;      /* frames per chunk (queries)                                             */
+    int32_t cache_frames;  /* sliding-window capacity in frames, the current chunk included          */
+    int32_t radius_h;      /* local window: max distance of block centres in tokens, per axis;       */
+    int32_t radius_w;      /*   negative = unbounded (Sec. 3.3)                                      */
+    int32_t window_mode;   /* LCSA_WINDOW_TRUNCATED: window cut at the frame border;                 */
+                           /* LCSA_WINDOW_PRESERVED: window keeps its size and slides inward (Fig. 3)*/
+    int32_t topk;          /* key blocks kept per (head, query block) (Sec. 3.2)                     */
+    int32_t dtype;         /* LCSA_F32 or LCSA_BF16: element type of Q, K, V, O and of the cache     */
+} lcsa_geom;
+
+/* ---- sliding-window KV cache (appendix "Discussion on Stream VSR Pipelines") ---------------- */
+
+typedef struct lcsa_cache lcsa_cache; /* host-side handle; the storage it describes is the caller's */
+
+/* Device bytes the caller must provide for one layer's cache; 0 if *geom is invalid. */
+size_t lcsa_cache_device_bytes(const lcsa_geom *geom);
+
+/*
+ * Creates a handle over caller-owned device memory (256-byte aligned, at least
+ * lcsa_cache_device_bytes(geom) bytes, contents irrelevant).  The cache starts empty.
+ * Host-only call.  LCSA_EINVAL on bad geometry, misaligned or undersized memory.
+ */
+int32_t lcsa_cache_init(lcsa_cache **out, const lcsa_geom *geom, void *device_mem, size_t bytes);
+/* Forgets all frames (start of a new video).  Host-only. */
+int32_t lcsa_cache_reset(lcsa_cache *cache);
+/* Frees the host handle; the device memory stays the caller's.  NULL is allowed. */
+void lcsa_cache_free(lcsa_cache *cache);
+/* Frames currently visible (0 .. cache_frames); negative status on NULL. */
+int32_t lcsa_cache_valid_frames(const lcsa_cache *cache);
+/*
+ * Inspection helpers for tests.  Pooled keys live in the cache as float
+ * [heads][cache_frames*nb][head_dim], indexed by ring slot: the block `tile` of visible
+ * frame f (0 = oldest) is row lcsa_cache_frame_slot(cache, f)*nb + tile.
+ */
+const float *lcsa_cache_pooled_k_device(const lcsa_cache *cache);
+int32_t lcsa_cache_frame_slot(const lcsa_cache *cache, int32_t frame);
+
+/*
+ * Appends the keys and values of n_frames new frames (device, raster order, the cache's
+ * dtype, shared strides) and evicts the oldest frames beyond the capacity: sliding-window
+ * eviction, the paper's default.  Also stores the block means of the new keys (Sec. 3.2
+ * average pooling) for lcsa_select_blocks.  1 <= n_frames <= cache_frames.
+ */
+int32_t lcsa_kv_cache_append(lcsa_cache *cache, const void *k, const void *v,
+                             int64_t stride_tok, int64_t stride_head,
+                             int32_t n_frames, void *stream);
+
+/* ---- block pooling (Sec. 3.2: average pooling inside each block) ------------------------------ */
+
+/*
+ * pooled[head][frame*nb + tile][c] = mean of x over the VALID tokens of the block
+ * (device float [heads][n_frames*nb][head_dim], written in full).  x: device, geom->dtype.
+ */
+int32_t lcsa_pool_blocks(const lcsa_geom *geom, const void *x,
+                         int64_t stride_tok, int64_t stride_head,
+                         int32_t n_frames, float *pooled, void *stream);
+
+/* ---- block selection (Sec. 3.2 coarse map + top-k, Sec. 3.3 / Fig. 3 local window) ----------- */
+
+/*
+ * For every (head, query block qb): scores S = <pooled_q[qb], pooled_k[kb]> (float
+ * accumulation) for every key block kb of every visible frame whose tile lies inside
+ * qb's spatial window; keeps the m = min(topk, #admissible) best, equal scores going to
+ * the lower key-block id.
+ *   sel_idx  device int32 [heads][q_frames*nb][topk]: kept ids ascending, then -1
+ *   sel_cnt  device int32 [heads][q_frames*nb]: m
+ *   gap      device float [heads][q_frames*nb] or NULL: score of the weakest kept block
+ *            minus the best admissible score left out (+inf if none is left out)
+ * pooled_q: device float [heads][q_frames*nb][head_dim] from lcsa_pool_blocks.
+ * The cache must hold at least q_frames frames.  At most 8192 admissible key blocks
+ * per row (LCSA_EUNSUPPORTED beyond).
+ */
+int32_t lcsa_select_blocks(const lcsa_geom *geom, const float *pooled_q, const lcsa_cache *cache,
+                           int32_t *sel_idx, int32_t *sel_cnt, float *gap, void *stream);
+
+/* ---- block-sparse attention (Sec. 3.2: full attention on the kept pairs; eq. 1) --------------- */
+
+/*
+ * o[token][head][:] = sum_j softmax_j(q_token . k_j * scale) v_j over the valid tokens j of
+ * the blocks sel_idx[head][block(token)][0 .. sel_cnt) (ids as produced against the cache's
+ * CURRENT contents).  q, o: device, geom->dtype, raster order over the chunk's q_frames
+ * frames, each with its own strides.  lse: device float [token][head] or NULL, natural
+ * log of the softmax denominator.  scale <= 0 selects 1/sqrt(head_dim).  Products are
+ * formed from the stored element type with float accumulation and a float online
+ * softmax; bf16 probabilities feed the second product on the matrix-core path.
+ * Rows with sel_cnt = 0 produce zeros (lse = -inf).
+ */
+int32_t lcsa_sparse_attn_fwd(const lcsa_geom *geom,
+                             const void *q, int64_t q_stride_tok, int64_t q_stride_head,
+                             const lcsa_cache *cache,
+                             const int32_t *sel_idx, const int32_t *sel_cnt,
+                             void *o, int64_t o_stride_tok, int64_t o_stride_head,
+                             float *lse, float scale, void *stream);
+
+/* Static, human-readable text for a status code. */
+const char *lcsa_status_string(int32_t status);
+/* Text of the last HIP error seen by this thread's most recent LCSA_EHIP ("" if none). */
+const char *lcsa_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LCSA_H */

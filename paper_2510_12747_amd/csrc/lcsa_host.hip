@@ -1,0 +1,210 @@
+// C ABI of the library (see include/lcsa.h): argument validation, the host-side ring
+// state of the sliding-window cache, and kernel dispatch.  No device allocation, no
+// synchronisation, no host<->device copies happen here.
+#include "../../include/lcsa.h"
+#include "lcsa_kernels.h"
+
+#include <new>
+#include <string>
+
+using namespace lcsa;
+
+struct lcsa_cache {
+    lcsa_geom geom;
+    KGeom kg;
+    KCache kc;
+    size_t bytes;
+};
+
+namespace {
+
+thread_local std::string g_last_hip_error;
+
+int32_t hip_status(hipError_t e) {
+    if (e == hipSuccess) return LCSA_OK;
+    g_last_hip_error = hipGetErrorString(e);
+    return LCSA_EHIP;
+}
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+bool geom_ok(const lcsa_geom *g) {
+    if (!g) return false;
+    if (g->dtype != LCSA_F32 && g->dtype != LCSA_BF16) return false;
+    const int vec = g->dtype == LCSA_BF16 ? 8 : 4;
+    if (g->heads < 1 || g->head_dim < 1 || g->head_dim > 256 || g->head_dim % vec) return false;
+    if (g->grid_h < 1 || g->grid_w < 1 || g->tile_h < 1 || g->tile_w < 1) return false;
+    if ((int64_t)g->tile_h * g->tile_w > 1024) return false;
+    if (g->q_frames < 1 || g->cache_frames < g->q_frames) return false;
+    if (g->window_mode != LCSA_WINDOW_TRUNCATED && g->window_mode != LCSA_WINDOW_PRESERVED) return false;
+    if (g->topk < 1) return false;
+    // index arithmetic in the kernels is 32-bit for block ids and 64-bit for elements
+    const int64_t ty = (g->grid_h + g->tile_h - 1) / g->tile_h, tx = (g->grid_w + g->tile_w - 1) / g->tile_w;
+    if (ty * tx * g->cache_frames > (1 << 24)) return false;
+    if ((int64_t)g->grid_h * g->grid_w * g->cache_frames > (1ll << 30)) return false;
+    return true;
+}
+
+KGeom derive(const lcsa_geom &g) {
+    KGeom k;
+    k.heads = g.heads; k.d = g.head_dim;
+    k.H = g.grid_h; k.W = g.grid_w; k.th = g.tile_h; k.tw = g.tile_w;
+    k.ty = (g.grid_h + g.tile_h - 1) / g.tile_h;
+    k.tx = (g.grid_w + g.tile_w - 1) / g.tile_w;
+    k.nb = k.ty * k.tx;
+    k.bt = g.tile_h * g.tile_w;
+    k.q_frames = g.q_frames; k.cap = g.cache_frames;
+    k.rh = g.radius_h; k.rw = g.radius_w; k.wmode = g.window_mode;
+    k.topk = g.topk;
+    k.bf16 = g.dtype == LCSA_BF16;
+    return k;
+}
+
+bool same_geom(const lcsa_geom *a, const lcsa_geom &b) {
+    return a->heads == b.heads && a->head_dim == b.head_dim && a->grid_h == b.grid_h && a->grid_w == b.grid_w &&
+           a->tile_h == b.tile_h && a->tile_w == b.tile_w && a->q_frames == b.q_frames &&
+           a->cache_frames == b.cache_frames && a->dtype == b.dtype;
+}
+
+struct Layout { size_t k_off, v_off, pooled_off, total; };
+
+Layout cache_layout(const KGeom &k) {
+    const size_t elt = k.bf16 ? 2 : 4;
+    const size_t tiles = (size_t)k.heads * k.cap * k.nb;
+    const size_t kv = align_up(tiles * k.bt * k.d * elt, 256);
+    Layout l;
+    l.k_off = 0;
+    l.v_off = kv;
+    l.pooled_off = 2 * kv;
+    l.total = 2 * kv + align_up(tiles * k.d * sizeof(float), 256);
+    return l;
+}
+
+bool tensor_ok(const void *p, int64_t st, int64_t sh, const KGeom &k) {
+    const int vec = k.bf16 ? 8 : 4;
+    if (!p || ((uintptr_t)p & 15)) return false;
+    if (st < k.d || sh < k.d || st % vec || sh % vec) return false;
+    return true;
+}
+
+} // namespace
+
+extern "C" {
+
+size_t lcsa_cache_device_bytes(const lcsa_geom *geom) {
+    if (!geom_ok(geom)) return 0;
+    return cache_layout(derive(*geom)).total;
+}
+
+int32_t lcsa_cache_init(lcsa_cache **out, const lcsa_geom *geom, void *device_mem, size_t bytes) {
+    if (!out || !geom_ok(geom) || !device_mem || ((uintptr_t)device_mem & 255)) return LCSA_EINVAL;
+    KGeom kg = derive(*geom);
+    Layout l = cache_layout(kg);
+    if (bytes < l.total) return LCSA_EINVAL;
+    lcsa_cache *c = new (std::nothrow) lcsa_cache;
+    if (!c) return LCSA_EINVAL;
+    c->geom = *geom;
+    c->kg = kg;
+    c->bytes = bytes;
+    char *base = (char *)device_mem;
+    c->kc.k = base + l.k_off;
+    c->kc.v = base + l.v_off;
+    c->kc.pooled = (float *)(base + l.pooled_off);
+    c->kc.start = 0;
+    c->kc.valid = 0;
+    c->kc.mfma_layout = kg.bf16 && kg.d == 128 && kg.bt == 128;
+    *out = c;
+    return LCSA_OK;
+}
+
+int32_t lcsa_cache_reset(lcsa_cache *cache) {
+    if (!cache) return LCSA_EINVAL;
+    cache->kc.start = 0;
+    cache->kc.valid = 0;
+    return LCSA_OK;
+}
+
+void lcsa_cache_free(lcsa_cache *cache) { delete cache; }
+
+int32_t lcsa_cache_valid_frames(const lcsa_cache *cache) {
+    return cache ? cache->kc.valid : (int32_t)LCSA_EINVAL;
+}
+
+const float *lcsa_cache_pooled_k_device(const lcsa_cache *cache) { return cache ? cache->kc.pooled : nullptr; }
+
+int32_t lcsa_cache_frame_slot(const lcsa_cache *cache, int32_t frame) {
+    if (!cache || frame < 0 || frame >= cache->kc.valid) return LCSA_EINVAL;
+    return slot_of_frame(cache->kc.start, cache->kg.cap, frame);
+}
+
+int32_t lcsa_kv_cache_append(lcsa_cache *cache, const void *k, const void *v,
+                             int64_t stride_tok, int64_t stride_head, int32_t n_frames, void *stream) {
+    if (!cache) return LCSA_EINVAL;
+    const KGeom &kg = cache->kg;
+    if (n_frames < 1 || n_frames > kg.cap) return LCSA_EINVAL;
+    if (!tensor_ok(k, stride_tok, stride_head, kg) || !tensor_ok(v, stride_tok, stride_head, kg)) return LCSA_EINVAL;
+    KCache &kc = cache->kc;
+    if ((int64_t)n_frames * kg.H * kg.W > (1ll << 30)) return LCSA_EINVAL;
+    // New frames go into the slots right after the newest frame; once the ring is full
+    // those are the slots of the oldest frames, which thereby leave the window.
+    const int first = slot_of_frame(kc.start, kg.cap, kc.valid);   // start + valid < 2*cap
+    hipError_t e = launch_append(kg, kc, k, v, stride_tok, stride_head, n_frames, first, (hipStream_t)stream);
+    if (e != hipSuccess) return hip_status(e);
+    const int evict = kc.valid + n_frames > kg.cap ? kc.valid + n_frames - kg.cap : 0;
+    kc.start = slot_of_frame(kc.start, kg.cap, evict);
+    kc.valid = kc.valid + n_frames - evict;
+    return LCSA_OK;
+}
+
+int32_t lcsa_pool_blocks(const lcsa_geom *geom, const void *x, int64_t stride_tok, int64_t stride_head,
+                         int32_t n_frames, float *pooled, void *stream) {
+    if (!geom_ok(geom) || !pooled || n_frames < 1) return LCSA_EINVAL;
+    KGeom kg = derive(*geom);
+    if (!tensor_ok(x, stride_tok, stride_head, kg)) return LCSA_EINVAL;
+    if ((int64_t)n_frames * kg.H * kg.W > (1ll << 30)) return LCSA_EINVAL;
+    return hip_status(launch_pool(kg, x, stride_tok, stride_head, n_frames, pooled, (hipStream_t)stream));
+}
+
+int32_t lcsa_select_blocks(const lcsa_geom *geom, const float *pooled_q, const lcsa_cache *cache,
+                           int32_t *sel_idx, int32_t *sel_cnt, float *gap, void *stream) {
+    if (!geom_ok(geom) || !cache || !pooled_q || !sel_idx || !sel_cnt) return LCSA_EINVAL;
+    if (!same_geom(geom, cache->geom)) return LCSA_EINVAL;
+    if (cache->kc.valid < geom->q_frames) return LCSA_EINVAL;
+    KGeom kg = derive(*geom);   // window, top-k may differ from the cache's own copy
+    const int mc = max_candidates(kg, cache->kc.valid);
+    if (mc > 8192) return LCSA_EUNSUPPORTED;
+    return hip_status(launch_select(kg, cache->kc, pooled_q, sel_idx, sel_cnt, gap, mc, (hipStream_t)stream));
+}
+
+int32_t lcsa_sparse_attn_fwd(const lcsa_geom *geom, const void *q, int64_t q_stride_tok, int64_t q_stride_head,
+                             const lcsa_cache *cache, const int32_t *sel_idx, const int32_t *sel_cnt,
+                             void *o, int64_t o_stride_tok, int64_t o_stride_head,
+                             float *lse, float scale, void *stream) {
+    if (!geom_ok(geom) || !cache || !sel_idx || !sel_cnt) return LCSA_EINVAL;
+    if (!same_geom(geom, cache->geom)) return LCSA_EINVAL;
+    if (cache->kc.valid < geom->q_frames) return LCSA_EINVAL;
+    KGeom kg = derive(*geom);
+    if (!tensor_ok(q, q_stride_tok, q_stride_head, kg) || !tensor_ok(o, o_stride_tok, o_stride_head, kg))
+        return LCSA_EINVAL;
+    if (!(scale > 0.f)) scale = 1.0f / sqrtf((float)kg.d);
+    hipError_t e = cache->kc.mfma_layout
+        ? launch_attn_mfma(kg, cache->kc, q, q_stride_tok, q_stride_head, sel_idx, sel_cnt,
+                           o, o_stride_tok, o_stride_head, lse, scale, (hipStream_t)stream)
+        : launch_attn_generic(kg, cache->kc, q, q_stride_tok, q_stride_head, sel_idx, sel_cnt,
+                              o, o_stride_tok, o_stride_head, lse, scale, (hipStream_t)stream);
+    return hip_status(e);
+}
+
+const char *lcsa_status_string(int32_t status) {
+    switch (status) {
+    case LCSA_OK: return "ok";
+    case LCSA_EINVAL: return "invalid argument";
+    case LCSA_EUNSUPPORTED: return "unsupported configuration";
+    case LCSA_EHIP: return "HIP runtime error";
+    default: return "unknown status";
+    }
+}
+
+const char *lcsa_last_hip_error(void) { return g_last_hip_error.c_str(); }
+
+} // extern "C"

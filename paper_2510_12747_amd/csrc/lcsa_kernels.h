@@ -1,0 +1,86 @@
+// Internal interface between the C-ABI host layer and the gfx950 kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace lcsa {
+
+// Geometry as the kernels see it (derived once per call on the host).
+struct KGeom {
+    int heads, d;
+    int H, W;          // token grid per frame
+    int th, tw;        // tile shape
+    int ty, tx, nb;    // tiles per frame: rows, cols, total
+    int bt;            // tokens per full tile = th*tw
+    int q_frames, cap; // chunk frames, ring capacity in frames
+    int rh, rw, wmode;
+    int topk;
+    int bf16;          // element type of Q,K,V,O and cache: 1 = bf16, 0 = f32
+};
+
+// Ring cache as the kernels see it.
+//   K tiles : [heads][cap][nb][tile image]   element type = geometry dtype
+//   V tiles : same extent
+//   pooled  : float [heads][cap*nb][d], indexed by ring slot
+// Tile image, generic layout: K and V row-major [bt][d], padded tokens zero.
+// Tile image, matrix-core layout (bf16, d = 128, bt = 128): 128 rows of 256 bytes,
+//   the 16-byte chunk j of row r stored at chunk position j ^ (r & 15);
+//   K rows = tile tokens (contents: d), V rows = channels (contents: tile tokens),
+//   i.e. V is stored transposed, and converted to IEEE half.  Padded tokens are zero in both.
+struct KCache {
+    void *k, *v;
+    float *pooled;
+    int start;   // ring slot of the oldest visible frame
+    int valid;   // visible frames
+    int mfma_layout;
+};
+
+__host__ __device__ inline int slot_of_frame(int start, int cap, int f) {
+    int s = start + f;
+    return s >= cap ? s - cap : s;
+}
+
+// Every launcher enqueues on `stream` and returns hipGetLastError().
+hipError_t launch_pool(const KGeom &g, const void *x, int64_t stride_tok, int64_t stride_head,
+                       int n_frames, float *pooled, hipStream_t stream);
+
+// Writes frames into ring slots first_slot.. (mod cap): tiles of K, V and pooled K.
+hipError_t launch_append(const KGeom &g, const KCache &c, const void *k, const void *v,
+                         int64_t stride_tok, int64_t stride_head, int n_frames, int first_slot,
+                         hipStream_t stream);
+
+hipError_t launch_select(const KGeom &g, const KCache &c, const float *pooled_q,
+                         int32_t *sel_idx, int32_t *sel_cnt, float *gap, int max_cand,
+                         hipStream_t stream);
+
+hipError_t launch_attn_generic(const KGeom &g, const KCache &c, const void *q, int64_t q_st, int64_t q_sh,
+                               const int32_t *sel_idx, const int32_t *sel_cnt,
+                               void *o, int64_t o_st, int64_t o_sh, float *lse, float scale,
+                               hipStream_t stream);
+
+hipError_t launch_attn_mfma(const KGeom &g, const KCache &c, const void *q, int64_t q_st, int64_t q_sh,
+                            const int32_t *sel_idx, const int32_t *sel_cnt,
+                            void *o, int64_t o_st, int64_t o_sh, float *lse, float scale,
+                            hipStream_t stream);
+
+// Largest number of admissible key blocks of any query block (host arithmetic).
+int max_candidates(const KGeom &g, int valid_frames);
+
+// Window of tile index b along one axis: [*lo, *hi).
+__host__ __device__ inline void axis_window(int b, int tile, int n, int radius, int mode, int *lo, int *hi) {
+    if (radius < 0) { *lo = 0; *hi = n; return; }
+    int r = radius / tile;              // centres are (b + 1/2)*tile apart by whole tiles
+    if (mode == 0) {
+        *lo = b - r < 0 ? 0 : b - r;
+        *hi = b + r + 1 > n ? n : b + r + 1;
+    } else {
+        int size = 2 * r + 1;
+        if (size >= n) { *lo = 0; *hi = n; return; }
+        int s = b - r;
+        if (s < 0) s = 0;
+        if (s > n - size) s = n - size;
+        *lo = s; *hi = s + size;
+    }
+}
+
+} // namespace lcsa

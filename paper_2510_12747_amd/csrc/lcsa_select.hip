@@ -1,0 +1,148 @@
+// Block selection: coarse block-to-block scores (Sec. 3.2) restricted to the spatial local
+// window (Sec. 3.3, Fig. 3), then the per-row top-k with ties going to the lower key-block
+// id.  One wavefront owns one (head, query block) row: lanes stride over the admissible key
+// blocks for the dot products, the k-th largest score is found by a 32-step bitwise search
+// over order-preserving integer keys with ballot/popcount, and the kept ids are emitted in
+// ascending order with ballot prefix counts.  No sort, no atomics, fully deterministic.
+#include "lcsa_kernels.h"
+
+namespace lcsa {
+namespace {
+
+// Monotone map float -> uint32 (larger float = larger key); -0 is folded into +0 first so
+// that equal floats always get equal keys.
+__device__ inline uint32_t order_key(float s) {
+    uint32_t u = __float_as_uint(s + 0.0f);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+__device__ inline float key_to_float(uint32_t key) {
+    return __uint_as_float((key & 0x80000000u) ? (key ^ 0x80000000u) : ~key);
+}
+
+__device__ inline int wave_count(bool p) { return __popcll(__ballot(p)); }
+
+__global__ __launch_bounds__(64) void select_kernel(KGeom g, KCache c, const float *__restrict__ pooled_q,
+                                                    int32_t *__restrict__ sel_idx, int32_t *__restrict__ sel_cnt,
+                                                    float *__restrict__ gap) {
+    extern __shared__ float smem[];
+    float *qs = smem;                                  // [d] pooled query of this row
+    uint32_t *keys = (uint32_t *)(smem + g.d);         // [n] ordered keys of the admissible blocks
+    const int qb = blockIdx.x, head = blockIdx.y, lane = threadIdx.x;
+    const int n_qb = g.q_frames * g.nb;
+    const int tile = qb % g.nb, by = tile / g.tx, bx = tile - by * g.tx;
+    int y0, y1, x0, x1;
+    axis_window(by, g.th, g.ty, g.rh, g.wmode, &y0, &y1);
+    axis_window(bx, g.tw, g.tx, g.rw, g.wmode, &x0, &x1);
+    const int wx = x1 - x0, nwin = (y1 - y0) * wx;
+    const int n = c.valid * nwin;                      // admissible key blocks, in ascending id order
+    const int64_t row = (int64_t)head * n_qb + qb;
+
+    for (int i = lane; i < g.d; i += 64) qs[i] = pooled_q[row * g.d + i];
+    __syncthreads();
+
+    // candidate ci -> (visible frame f, tile t); key-block id = f*nb + t grows with ci
+    auto tile_of = [&](int ci, int &f) {
+        f = ci / nwin;
+        int w = ci - f * nwin, wy = w / wx;
+        return (y0 + wy) * g.tx + x0 + (w - wy * wx);
+    };
+
+    for (int ci = lane; ci < n; ci += 64) {
+        int f;
+        const int t = tile_of(ci, f);
+        const int slot = slot_of_frame(c.start, g.cap, f);
+        const float4 *kr = (const float4 *)(c.pooled + (((int64_t)head * g.cap + slot) * g.nb + t) * g.d);
+        float s = 0.f;
+        for (int e = 0; e < g.d / 4; ++e) {
+            const float4 kk = kr[e];
+            s = fmaf(qs[4 * e], kk.x, s);
+            s = fmaf(qs[4 * e + 1], kk.y, s);
+            s = fmaf(qs[4 * e + 2], kk.z, s);
+            s = fmaf(qs[4 * e + 3], kk.w, s);
+        }
+        keys[ci] = order_key(s);
+    }
+    __syncthreads();
+
+    int32_t *out = sel_idx + row * g.topk;
+    const int k = g.topk;
+    const uint64_t lt_mask = (1ull << lane) - 1ull;
+    int written = 0;
+    float row_gap = __builtin_inff();
+
+    if (n <= k) {
+        for (int base = 0; base < n; base += 64) {
+            const int ci = base + lane;
+            if (ci < n) { int f; const int t = tile_of(ci, f); out[ci] = f * g.nb + t; }
+        }
+        written = n;
+    } else {
+        // T = k-th largest key: the largest value with at least k keys >= it
+        uint32_t T = 0;
+        for (int bit = 31; bit >= 0; --bit) {
+            const uint32_t trial = T | (1u << bit);
+            int cnt = 0;
+            for (int base = 0; base < n; base += 64) {
+                const int ci = base + lane;
+                cnt += wave_count(ci < n && keys[ci] >= trial);
+            }
+            if (cnt >= k) T = trial;
+        }
+        int n_gt = 0, n_ge = 0;
+        uint32_t below = 0;                              // largest key < T (0 if none; keys of finite floats are > 0)
+        for (int base = 0; base < n; base += 64) {
+            const int ci = base + lane;
+            const uint32_t key = ci < n ? keys[ci] : 0u;
+            n_gt += wave_count(ci < n && key > T);
+            n_ge += wave_count(ci < n && key >= T);
+            if (ci < n && key < T && key > below) below = key;
+        }
+        const int need = k - n_gt;                       // how many of the blocks tied at T are kept (>= 1)
+        int eq_seen = 0;
+        for (int base = 0; base < n; base += 64) {
+            const int ci = base + lane;
+            const uint32_t key = ci < n ? keys[ci] : 0u;
+            const bool gt = ci < n && key > T, eq = ci < n && key == T;
+            const uint64_t eq_mask = __ballot(eq);
+            const bool keep = gt || (eq && eq_seen + __popcll(eq_mask & lt_mask) < need);
+            const uint64_t keep_mask = __ballot(keep);
+            if (keep) { int f; const int t = tile_of(ci, f); out[written + __popcll(keep_mask & lt_mask)] = f * g.nb + t; }
+            written += __popcll(keep_mask);
+            eq_seen += __popcll(eq_mask);
+        }
+        if (gap) {
+            if (n_ge > k) row_gap = 0.f;
+            else {
+                for (int off = 32; off > 0; off >>= 1) {
+                    const uint32_t o = __shfl_xor(below, off);
+                    below = o > below ? o : below;
+                }
+                row_gap = key_to_float(T) - key_to_float(below);
+            }
+        }
+    }
+    for (int i = written + lane; i < k; i += 64) out[i] = -1;
+    if (lane == 0) {
+        sel_cnt[row] = written;
+        if (gap) gap[row] = row_gap;
+    }
+}
+
+} // namespace
+
+int max_candidates(const KGeom &g, int valid_frames) {
+    int my = 0, mx = 0;
+    for (int b = 0; b < g.ty; ++b) { int lo, hi; axis_window(b, g.th, g.ty, g.rh, g.wmode, &lo, &hi); if (hi - lo > my) my = hi - lo; }
+    for (int b = 0; b < g.tx; ++b) { int lo, hi; axis_window(b, g.tw, g.tx, g.rw, g.wmode, &lo, &hi); if (hi - lo > mx) mx = hi - lo; }
+    return my * mx * valid_frames;
+}
+
+hipError_t launch_select(const KGeom &g, const KCache &c, const float *pooled_q,
+                         int32_t *sel_idx, int32_t *sel_cnt, float *gap, int max_cand, hipStream_t stream) {
+    dim3 grid(g.q_frames * g.nb, g.heads);
+    const size_t lds = (size_t)(g.d + max_cand) * sizeof(float);
+    select_kernel<<<grid, 64, lds, stream>>>(g, c, pooled_q, sel_idx, sel_cnt, gap);
+    return hipGetLastError();
+}
+
+} // namespace lcsa

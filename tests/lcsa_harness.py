@@ -1,0 +1,162 @@
+"""Shared driver for the GPU parity tests: runs one stream of chunks through the HIP
+library and through the CPU oracle on identical inputs and compares the results."""
+from __future__ import annotations
+
+import sys
+from dataclasses import dataclass
+
+import numpy as np
+import torch
+
+import oracle
+from paper_2510_12747_amd import binding as B
+from paper_2510_12747_amd import workloads as wl
+
+NEAR_TIE = 1e-3          # selection may differ from the oracle only where its score gap is below this
+OUT_MAX_ABS = 1e-2       # output tolerances from the benchmark definition (unit-variance V)
+OUT_MEAN_ABS = 1e-3
+
+
+def say(msg: str) -> None:
+    """Progress line, flushed, so that a run that dies on the GPU still names its case."""
+    print(f"[lcsa] {msg}", file=sys.stderr, flush=True)
+
+
+def to_device(x: np.ndarray, dtype: str, layout: str = "thd") -> torch.Tensor:
+    """float32 host array [tokens][heads][d] -> device tensor viewed as [tokens][heads][d].
+    layout "thd": token-major storage; "htd": head-major storage (strided view)."""
+    if dtype == "bf16":
+        t = torch.from_numpy(wl.bf16_bits(x).view(np.int16)).view(torch.bfloat16)
+    else:
+        t = torch.from_numpy(np.ascontiguousarray(x, np.float32))
+    if layout == "htd":
+        return t.permute(1, 0, 2).contiguous().cuda().permute(1, 0, 2)
+    return t.cuda()
+
+
+def geoms(w: wl.Workload, topk=None, radius=None, window_mode=0):
+    """(library geometry, oracle geometry) of a workload."""
+    k = w.topk if topk is None else topk
+    r = w.radius if radius is None else radius
+    rh, rw = (r, r) if np.isscalar(r) else r
+    g = B.Geom(w.heads, w.head_dim, w.grid_h, w.grid_w, w.tile_h, w.tile_w, w.q_frames, w.cache_frames,
+               rh, rw, k, dtype=B.LCSA_BF16 if w.dtype == "bf16" else B.LCSA_F32, window_mode=window_mode)
+    og = oracle.Geometry(w.heads, w.head_dim, w.grid_h, w.grid_w, w.tile_h, w.tile_w, w.q_frames, rh, rw, k,
+                         window_mode=window_mode)
+    return g, og
+
+
+def sample_rows(og: oracle.Geometry, n_random: int, seed: int = 0) -> np.ndarray:
+    """(head, query block) rows to verify at sizes where the oracle cannot do them all:
+    every corner / edge-centre tile of each query frame for head 0 and the last head, plus random rows."""
+    ty = -(-og.grid_h // og.tile_h)
+    tx = -(-og.grid_w // og.tile_w)
+    nb = ty * tx
+    tiles = {(by, bx) for by in (0, ty // 2, ty - 1) for bx in (0, tx // 2, tx - 1)}
+    rows = {(h, f * nb + by * tx + bx) for h in {0, og.heads - 1} for f in range(og.q_frames) for by, bx in tiles}
+    rng = np.random.default_rng(seed)
+    while len(rows) < len(tiles) * og.q_frames * len({0, og.heads - 1}) + n_random:
+        rows.add((int(rng.integers(og.heads)), int(rng.integers(og.q_frames * nb))))
+    return np.array(sorted(rows), np.int32)
+
+
+@dataclass
+class StepResult:
+    sel_mismatch_rows: int       # rows whose set differs from the oracle's (all of them near-ties, else assert)
+    near_tie_rows: int           # rows with oracle gap < NEAR_TIE
+    max_abs: float
+    mean_abs: float
+    rows_checked: int
+
+
+def check_selection(sel_idx, sel_cnt, o_idx, o_cnt, o_gap, og, kv_frames):
+    """Bit-exact selection except rows whose oracle gap is below NEAR_TIE; every GPU row must
+    still be a valid selection (ascending, unique, admissible, right count, -1 padded)."""
+    sel_idx, sel_cnt = sel_idx.cpu().numpy(), sel_cnt.cpu().numpy()
+    np.testing.assert_array_equal(sel_cnt, o_cnt)
+    diff = (sel_idx != o_idx).any(axis=-1)
+    near = o_gap < NEAR_TIE
+    bad = diff & ~near
+    assert not bad.any(), f"{bad.sum()} rows differ from the oracle with gap >= {NEAR_TIE}: first {np.argwhere(bad)[:5]}"
+    for h, qb in np.argwhere(diff):
+        m = sel_cnt[h, qb]
+        kept = sel_idx[h, qb, :m]
+        assert (np.diff(kept) > 0).all() and (sel_idx[h, qb, m:] == -1).all()
+        assert all(oracle.allowed(int(qb), int(kb), og) for kb in kept) and kept.max() < kv_frames * og.nb
+    return sel_idx, sel_cnt, int(diff.sum()), int(near.sum())
+
+
+def check_outputs(o_gpu: torch.Tensor, q, K, V, og, kv_frames, sel_idx, sel_cnt, rows, scale=0.0,
+                  max_abs=OUT_MAX_ABS, mean_abs=OUT_MEAN_ABS):
+    """Compares against the oracle's attention on the SAME selection (the GPU's, which equals the
+    oracle's except on reported near-tie rows)."""
+    want = oracle.attend(q, K, V, og, kv_frames, sel_idx, sel_cnt, scale=scale, rows=rows)
+    got = o_gpu.float().cpu().numpy().astype(np.float64)
+    done = ~np.isnan(want)
+    assert done.any()
+    err = np.abs(got - want)[done]
+    assert np.isfinite(got[done]).all()
+    assert err.max() <= max_abs, f"max-abs {err.max():.3e} > {max_abs}"
+    assert err.mean() <= mean_abs, f"mean-abs {err.mean():.3e} > {mean_abs}"
+    return float(err.max()), float(err.mean())
+
+
+class Pipeline:
+    """One layer's state on both sides: the library's cache and the oracle's list model."""
+
+    def __init__(self, w: wl.Workload, layer: int = 0, layout: str = "thd", **geom_kw):
+        self.w, self.layout = w, layout
+        self.g, self.og = geoms(w, **geom_kw)
+        self.stream = wl.ChunkStream(w, layer)
+        self.cache = B.lcsa_cache_init(self.g)
+        self.model = oracle.SlidingWindowCache(w.cache_frames)
+        self.chunk = 0
+
+    def feed(self, q=None, k=None, v=None):
+        """Appends the next chunk on both sides; returns (q host, q device)."""
+        if q is None:
+            q, k, v = self.stream.next()
+        w = self.w
+        self.model.append(k, v, w.q_frames)
+        B.lcsa_kv_cache_append(self.cache, to_device(k, w.dtype, self.layout), to_device(v, w.dtype, self.layout), w.q_frames)
+        assert B.lcsa_cache_valid_frames(self.cache) == self.model.valid_frames
+        self.chunk += 1
+        return q, to_device(q, w.dtype, self.layout)
+
+    def check_pooled_k(self, tol=2e-5):
+        K, _ = self.model.visible()
+        want = oracle.pool(K, self.og, self.model.valid_frames)
+        got = B.lcsa_cache_pooled_k(self.cache).cpu().numpy()
+        nb = self.g.nb
+        for f in range(self.model.valid_frames):
+            s = B.lcsa_cache_frame_slot(self.cache, f)
+            np.testing.assert_allclose(got[:, s * nb:(s + 1) * nb], want[:, f * nb:(f + 1) * nb], rtol=0, atol=tol)
+
+    def step(self, q, qd, rows=None, g=None, og=None, scale=0.0, max_abs=OUT_MAX_ABS, mean_abs=OUT_MEAN_ABS,
+             check_lse=False) -> StepResult:
+        """pool -> select -> attend on the GPU, the same on the oracle, compare."""
+        g = g or self.g
+        og = og or self.og
+        kvf = self.model.valid_frames
+        K, V = self.model.visible()
+        pq = B.lcsa_pool_blocks(g, qd, g.q_frames)
+        sel_idx, sel_cnt, gap = B.lcsa_select_blocks(g, pq, self.cache)
+        lse = torch.empty(qd.shape[0], g.heads, dtype=torch.float32, device="cuda") if check_lse else None
+        o = B.lcsa_sparse_attn_fwd(g, qd, self.cache, sel_idx, sel_cnt, lse=lse, scale=scale)
+        torch.cuda.synchronize()
+        o_pq = oracle.pool(q, og, g.q_frames)
+        np.testing.assert_allclose(pq.cpu().numpy(), o_pq, rtol=0, atol=2e-5)
+        S = oracle.scores(o_pq, oracle.pool(K, og, kvf))
+        o_idx, o_cnt, o_gap = oracle.select(S, og, kvf)
+        s_idx, s_cnt, n_diff, n_near = check_selection(sel_idx, sel_cnt, o_idx, o_cnt, o_gap, og, kvf)
+        ggap = gap.cpu().numpy()
+        fin = np.isfinite(o_gap)
+        assert (np.isinf(ggap) == ~fin).all()
+        np.testing.assert_allclose(ggap[fin], o_gap[fin], rtol=0, atol=1e-3)
+        mx, mean = check_outputs(o, q, K, V, og, kvf, s_idx, s_cnt, rows, scale, max_abs, mean_abs)
+        if check_lse:
+            _, want_lse = oracle.attend(q, K, V, og, kvf, s_idx, s_cnt, scale=scale, rows=rows, with_lse=True)
+            done = ~np.isnan(want_lse)
+            np.testing.assert_allclose(lse.cpu().numpy()[done], want_lse[done], rtol=0, atol=2e-3)
+        n_rows = g.heads * g.q_frames * g.nb if rows is None else len(rows)
+        return StepResult(n_diff, n_near, mx, mean, n_rows)
