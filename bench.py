@@ -1,0 +1,229 @@
+#!/usr/bin/env python3
+"""Benchmark of the locality-constrained block-sparse attention hot path on one MI355X.
+
+One STEP = one chunk of latent frames through every layer of the workload: per layer
+lcsa_kv_cache_append -> lcsa_pool_blocks -> lcsa_select_blocks -> lcsa_sparse_attn_fwd, each
+layer with its own seeded Q/K/V and its own sliding-window cache (already primed, so the timed
+step runs in steady state: append evicts the oldest frames, attention sees a full window).
+Inputs are resident in HBM before the timed region.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload paper|small|ultra|4k]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+from concurrent.futures import ThreadPoolExecutor
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 / fp16 matrix peak
+PEAK_HBM_GBS = 8000.0
+
+WORKLOAD_TEXT = {
+    "paper": "paper-scale 768x1408: 48x88 tokens/frame, 2 query + 4 cached frames, 8x16 tiles, radius 24, top-k 32, 30 layer calls",
+    "small": "small-video 384x704: 24x44 tokens/frame, 2 query + 4 cached frames, 8x16 tiles, radius 16, top-k 16",
+    "ultra": "ultra-high-res 1440x2560: 90x160 tokens/frame, 2 query + 4 cached frames, 8x16 tiles, radius 24, top-k 32",
+    "4k": "4k streaming 2160x3840: 135x240 tokens/frame, 1 query frame, ring of 6 frames, 8x16 tiles, radius 24, top-k 32",
+}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="paper", choices=sorted(WORKLOAD_TEXT))
+    ap.add_argument("--layers", type=int, default=0, help="override the workload's number of layer calls")
+    ap.add_argument("--topk", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build measures ONE GPU (the path has no inter-GPU part); run with --gpus 1", file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2510_12747_amd import binding as B
+    from paper_2510_12747_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    B.lib()   # fail loudly if the HIP library is not built
+
+    w = wl.WORKLOADS[args.workload]
+    n_layers = args.layers or w.n_layers
+    topk = args.topk or w.topk
+    g = B.Geom(w.heads, w.head_dim, w.grid_h, w.grid_w, w.tile_h, w.tile_w, w.q_frames, w.cache_frames,
+               w.radius, w.radius, topk, dtype=B.LCSA_BF16)
+    n_qb = g.q_frames * g.nb
+
+    def dev(x):
+        return torch.from_numpy(wl.bf16_bits(x).view(np.int16)).view(torch.bfloat16).cuda()
+
+    # ---- setup: seeded inputs per layer (host, threads), caches primed ---------------------------
+    t0 = time.time()
+
+    def gen(layer):
+        s = wl.ChunkStream(w, layer)
+        return [s.next() for _ in range(w.prime_chunks + 1)]
+
+    layers = []
+    host_layer0 = None
+    with ThreadPoolExecutor(max_workers=min(8, os.cpu_count() or 1)) as pool:
+        for layer, chunks in enumerate(pool.map(gen, range(n_layers))):
+            cache = B.lcsa_cache_init(g)
+            dchunks = [tuple(dev(x) for x in c) for c in chunks]
+            # fill the ring with all chunks of the stream; a timed step then re-appends them in turn,
+            # so the window always holds the same frames (a static scene) and every append evicts
+            for (qd, kd, vd) in dchunks:
+                B.lcsa_kv_cache_append(cache, kd, vd, w.q_frames)
+            layers.append(dict(
+                cache=cache, chunks=dchunks, turn=0,
+                pq=torch.empty(g.heads, n_qb, g.head_dim, dtype=torch.float32, device="cuda"),
+                sel_idx=torch.empty(g.heads, n_qb, topk, dtype=torch.int32, device="cuda"),
+                sel_cnt=torch.empty(g.heads, n_qb, dtype=torch.int32, device="cuda"),
+                o=torch.empty_like(dchunks[0][0])))
+            if layer == 0:
+                host_layer0 = chunks
+    torch.cuda.synchronize()
+    setup_s = time.time() - t0
+
+    def layer_call(L, ev=None, attn_ev=None):
+        q, k, v = L["chunks"][L["turn"] % len(L["chunks"])]
+        L["turn"] += 1
+        B.lcsa_kv_cache_append(L["cache"], k, v, w.q_frames)
+        if ev: ev[0].record()
+        B.lcsa_pool_blocks(g, q, w.q_frames, L["pq"])
+        if ev: ev[1].record()
+        B.lcsa_select_blocks(g, L["pq"], L["cache"], L["sel_idx"], L["sel_cnt"], want_gap=False)
+        if ev: ev[2].record()
+        if attn_ev: attn_ev[0].record()
+        B.lcsa_sparse_attn_fwd(g, q, L["cache"], L["sel_idx"], L["sel_cnt"], L["o"])
+        if attn_ev: attn_ev[1].record()
+        if ev: ev[3].record()
+
+    for _ in range(args.warmup):
+        for L in layers:
+            layer_call(L)
+    torch.cuda.synchronize()
+
+    # ---- timed region: exactly K steps; HIP events around every attention launch ------------------
+    # (all launches go to torch's current stream, which is the stream these events are recorded on)
+    attn_ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in layers]
+               for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    for s in range(args.steps):
+        for L, (e0, e1) in zip(layers, attn_ev[s]):
+            layer_call(L, attn_ev=(e0, e1))
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t_start
+    ms_per_step = elapsed * 1e3 / args.steps
+    ms_per_layer = ms_per_step / n_layers
+    attn_ms = np.array([[e0.elapsed_time(e1) for (e0, e1) in step] for step in attn_ev])
+
+    # ---- untimed breakdown pass: events between the four calls ------------------------------------
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in layers]
+    for L, e in zip(layers, ev):
+        e[4].record()
+        layer_call(L, e)
+    torch.cuda.synchronize()
+    brk = np.array([[e[4].elapsed_time(e[0]), e[0].elapsed_time(e[1]), e[1].elapsed_time(e[2]), e[2].elapsed_time(e[3])]
+                    for e in ev]).mean(axis=0)
+
+    # ---- algorithmic work of one attention launch (from the selection actually made) ---------------
+    ty, tx = -(-w.grid_h // w.tile_h), -(-w.grid_w // w.tile_w)
+    vh = np.minimum(w.tile_h, w.grid_h - np.arange(ty) * w.tile_h)
+    vw = np.minimum(w.tile_w, w.grid_w - np.arange(tx) * w.tile_w)
+    valid_tok = (vh[:, None] * vw[None, :]).reshape(-1)              # valid tokens per tile
+    useful, issued = [], []
+    for L in layers:
+        idx = L["sel_idx"].cpu().numpy()
+        cnt = L["sel_cnt"].cpu().numpy()
+        kvalid = np.where(idx >= 0, valid_tok[np.maximum(idx, 0) % g.nb], 0).sum(axis=-1)   # [h][qb]
+        qvalid = valid_tok[np.arange(n_qb) % g.nb][None, :]
+        useful.append(4.0 * g.head_dim * float((qvalid * kvalid).sum()))
+        issued.append(4.0 * 128 * 128 * g.head_dim * float(cnt.sum()))
+    useful_flop, issued_flop = float(np.mean(useful)), float(np.mean(issued))
+    attn_avg_ms = float(attn_ms.mean())
+    achieved = useful_flop / (attn_avg_ms * 1e-3) / 1e12
+
+    # append traffic (algorithmic): read new K,V once, write their tiles once, write pooled K
+    tok_new = w.q_frames * w.tokens_per_frame
+    append_bytes = 2 * tok_new * g.heads * g.head_dim * 2 + 2 * w.q_frames * g.nb * 128 * 128 * 2 * g.heads \
+        + w.q_frames * g.nb * g.heads * g.head_dim * 4
+    pool_bytes = tok_new * g.heads * g.head_dim * 2 + n_qb * g.heads * g.head_dim * 4
+
+    out = {
+        "metric": "sparse_attn_ms_per_chunk_per_layer",
+        "value": round(ms_per_layer, 5),
+        "unit": "ms",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": False,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": WORKLOAD_TEXT[args.workload], "heads": g.heads, "head_dim": g.head_dim,
+                   "layers_per_step": n_layers, "q_tokens": tok_new, "kv_tokens": w.cache_frames * w.tokens_per_frame,
+                   "blocks_per_frame": g.nb, "topk": topk},
+        "effective_tflops_whole_path": round(useful_flop / (ms_per_layer * 1e-3) / 1e12, 2),
+        "kernel_ms_per_layer": {"kv_cache_append": round(float(brk[0]), 5), "pool_blocks": round(float(brk[1]), 5),
+                                "select_blocks": round(float(brk[2]), 5), "sparse_attn_fwd": round(attn_avg_ms, 5)},
+        "hbm_gbs": {"kv_cache_append": round(append_bytes / (brk[0] * 1e-3) / 1e9, 1),
+                    "pool_blocks": round(pool_bytes / (brk[1] * 1e-3) / 1e9, 1)},
+        "roofline": {"kernel": "attn_mfma_kernel", "bound": "mfma", "achieved": round(achieved, 2),
+                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
+                     "traffic": None,
+                     "flop_per_launch_useful": useful_flop, "flop_per_launch_issued": issued_flop,
+                     "issued_tflops": round(issued_flop / (attn_avg_ms * 1e-3) / 1e12, 2),
+                     "avg_launch_ms": round(attn_avg_ms, 5), "min_launch_ms": round(float(attn_ms.min()), 5)},
+        "setup_s": round(setup_s, 1),
+    }
+
+    # ---- CPU oracle on the host cores: a bounded sample of the same workload ------------------------
+    if not args.no_cpu_baseline:
+        import oracle
+        og = oracle.Geometry(w.heads, w.head_dim, w.grid_h, w.grid_w, w.tile_h, w.tile_w, w.q_frames,
+                             w.radius, w.radius, topk)
+        model = oracle.SlidingWindowCache(w.cache_frames)
+        for (q, k, v) in host_layer0:
+            model.append(k, v, w.q_frames)
+        K, V = model.visible()
+        q = host_layer0[-1][0]
+        # rows of the sample: every (head, query block) of layer 0 if that fits ~30 s, else a prefix
+        rows = np.array([(h, qb) for qb in range(n_qb) for h in range(g.heads)], np.int32)
+        t1 = time.perf_counter()
+        probe = oracle.lcsa(q, K, V, og, model.valid_frames, rows=rows[:16])
+        t_probe = time.perf_counter() - t1
+        sel_t = 0.0
+        t1 = time.perf_counter()
+        pq, pk = oracle.pool(q, og, g.q_frames), oracle.pool(K, og, model.valid_frames)
+        o_idx, o_cnt, _ = oracle.select(oracle.scores(pq, pk), og, model.valid_frames)
+        sel_t = time.perf_counter() - t1
+        per_row = max((t_probe - sel_t) / 16, 1e-4)
+        n_sample = int(min(len(rows), max(16, 20.0 / per_row)))
+        t1 = time.perf_counter()
+        oracle.attend(q, K, V, og, model.valid_frames, o_idx, o_cnt, rows=rows[:n_sample])
+        att_t = time.perf_counter() - t1
+        layer_s = sel_t + att_t * len(rows) / n_sample
+        out["cpu_baseline"] = {"value": round(layer_s * 1e3, 1), "unit": "ms", "cores": oracle.threads(), "kind": "oracle",
+                               "sample": f"layer 0 of the same workload: pooling, scores and selection in full "
+                                         f"({sel_t:.2f} s), attention on {n_sample} of {len(rows)} (head, query-block) rows "
+                                         f"({att_t:.2f} s) scaled to the full layer"}
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
