@@ -43,6 +43,8 @@ def main() -> int:
     ap.add_argument("--layers", type=int, default=0, help="override the workload's number of layer calls")
     ap.add_argument("--topk", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one 1 GiB device-to-device copy (reference point for HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures ONE GPU (the path has no inter-GPU part); run with --gpus 1", file=sys.stderr)
@@ -108,6 +110,13 @@ def main() -> int:
         B.lcsa_sparse_attn_fwd(g, q, L["cache"], L["sel_idx"], L["sel_cnt"], L["o"])
         if attn_ev: attn_ev[1].record()
         if ev: ev[3].record()
+
+    if args.calibrate_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         for L in layers:

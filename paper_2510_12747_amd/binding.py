@@ -14,7 +14,8 @@ from dataclasses import dataclass
 import torch  # imported first so that the HIP runtime torch ships is the one the library binds to
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "liblcsa.so")
+# LCSA_LIBRARY may name another build of the same library (e.g. an experimental kernel variant)
+LIB_PATH = os.environ.get("LCSA_LIBRARY") or os.path.join(_HERE, "liblcsa.so")
 
 LCSA_F32, LCSA_BF16 = 0, 1
 WINDOW_TRUNCATED, WINDOW_PRESERVED = 0, 1

@@ -1,54 +1,66 @@
 // Block-sparse flash attention on the gfx950 matrix cores (bf16, d = 128, 128-token blocks).
 //
-// One workgroup (4 wavefronts) owns one (head, query block); wavefront w owns query rows
-// 32w .. 32w+31.  For each selected key block the K tile and the transposed V tile (each a
-// 32 KB byte-for-byte LDS image prepared by the cache append) are streamed into LDS with
-// direct-to-LDS loads, and the wavefront computes
-//     S^T = K Q^T          v_mfma_f32_32x32x16_bf16  (keys on the row axis, queries on lanes)
-//     O^T += V^T P^T       v_mfma_f32_32x32x16_f16   (channels on the row axis, queries on lanes)
+// Work item = one (head, query block): 128 query rows against its selected key blocks.
+// A workgroup has 8 wavefronts = two GROUPS of 4; each group owns one work item (the two
+// query frames of the same spatial tile, which share their window), its own K and V tile
+// buffers in LDS, and wavefront w of a group owns query rows 32w .. 32w+31.
+//
+// Per selected key block a group runs three stages
+//     QK   S^T = K Q^T        v_mfma_f32_32x32x16_bf16  (keys on the row axis, queries on lanes)
+//     SM   online softmax     VALU, fp32 (eq. 1; scale folded into exp2; lazily updated reference)
+//     PV   O^T += V^T P^T     v_mfma_f32_32x32x16_f16   (channels on the row axis, queries on lanes)
+// and the two groups run one stage apart, every stage ending in a workgroup barrier: each
+// SIMD holds one wavefront of either group, so while one issues matrix instructions the
+// other mostly issues vector instructions.  Left to themselves two independent wavefronts
+// fall into step (both want the matrix pipe, then both want the vector pipe); the fixed
+// stagger keeps the two pipes busy together.
+//
+// Transposed products put every query column in one lane (and its partner lane^32): the
+// softmax statistics need one cross-lane exchange per block, the rescale factor of O is a
+// per-lane scalar, and the accumulator of S^T is already in B-operand layout for the second
+// product.  K rows fed to MFMA row m are permuted (bits 2 and 3 of m swapped) so that
+// accumulator registers 8s..8s+7 of a lane hold 8 consecutive keys: the P fragment for
+// k-step s is those registers packed, the matching V^T fragment one 16-byte LDS read.
+//
 // The second product runs in IEEE half (same matrix-core rate as bf16): probabilities lie in
 // [0,1] and need mantissa rather than range, which cuts the kernel's dominant rounding error
 // (bf16 P) by 8x; V was converted to half, exactly for all normal-range values, at append time.
-// so that every query column lives in one lane (and its partner lane+32): the online-softmax
-// statistics (eq. 1, scale folded into exp2) need no cross-lane traffic beyond one exchange
-// with lane^32, the accumulator of S^T is already in B-operand layout for the second product,
-// and the rescale factor of O is a per-lane scalar.
 //
-// The K rows fed to MFMA row m are permuted (bits 2 and 3 of m swapped) so that accumulator
-// registers 8s..8s+7 of a lane hold 8 consecutive keys: the bf16 P fragment for k-step s is
-// then just those registers packed, and the matching V^T fragment is one 16-byte LDS read.
+// K and V tiles are 32 KB byte-for-byte LDS images prepared by the cache append (16-byte
+// chunk j of row r at chunk position j ^ (r & 15): conflict-free ds_read_b128 operand reads)
+// and are streamed in with direct-to-LDS loads that stay in flight across barriers:
+// V(i) arrives during QK(i)+SM(i), K(i+1) during SM(i)+PV(i).
 #include "lcsa_kernels.h"
 
 namespace lcsa {
 namespace {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
+typedef __attribute__((ext_vector_type(2))) _Float16 f16x2;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 
 constexpr int kTileBytes = 128 * 256;
+constexpr int kAhead = 6;            // operand fragments in flight ahead of the matrix instruction using them
+constexpr int kRing = kAhead + 1;
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 
-#define LCSA_GLOBAL __attribute__((address_space(1)))
 #define LCSA_LDS __attribute__((address_space(3)))
 
-// Synchronisation inside the main loop is written as inline assembly on purpose.  The tile
-// copies are direct-to-LDS loads that stay in flight across workgroup barriers; __syncthreads()
-// and the compiler's own bookkeeping for LDS-writing loads would drain them (vmcnt(0)) at every
-// barrier and before unrelated LDS reads, which serialises copy and compute.  Here arrival of a
-// tile is established by an explicit vmcnt wait, and the barrier only orders LDS traffic.
-//   vm_allow = number of newer vector-memory loads that may still be in flight.
-template <int VM_ALLOW>
-__device__ inline void wait_tiles_and_barrier() {
-    static_assert(VM_ALLOW == 0 || VM_ALLOW == 8, "encodable cases used by the kernel");
-    if (VM_ALLOW == 0) asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
-    else asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)\n\ts_barrier" ::: "memory");
-}
-__device__ inline void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+// Synchronisation inside the main loop is inline assembly on purpose.  The tile copies are
+// direct-to-LDS loads that stay in flight across workgroup barriers; __syncthreads() and the
+// compiler's own bookkeeping for LDS-writing loads would drain them (vmcnt(0)) at every
+// barrier and before unrelated LDS reads, which serialises copy and compute.  Arrival of a
+// tile is established by an explicit vmcnt wait; the barrier itself only orders LDS traffic.
+__device__ inline void stage_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+// wait until at most N of this wavefront's vector-memory loads are still in flight
+__device__ inline void wait_vm0() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+__device__ inline void wait_vm8() { asm volatile("s_waitcnt vmcnt(8)" ::: "memory"); }
 
-// Each wavefront copies its quarter (8 KB) of a 32 KB tile image: 8 loads of 64 lanes x 16
-// bytes; lane t of a load lands at LDS address M0 + 16*t.
+// Each wavefront of a group copies its quarter (8 KB) of a 32 KB tile image: 8 loads of
+// 64 lanes x 16 bytes; lane t of a load lands at LDS address M0 + 16*t.
 __device__ inline void tile_to_lds(const char *gsrc, unsigned char *lds, int wave, int lane) {
     const char *gp = gsrc + wave * 8192 + lane * 16;
     uint32_t dst = (uint32_t)(uintptr_t)((LCSA_LDS unsigned char *)lds) + wave * 8192;
@@ -59,63 +71,128 @@ __device__ inline void tile_to_lds(const char *gsrc, unsigned char *lds, int wav
                      :: "v"(gp + i * 1024), "s"(dst + i * 1024) : "memory", "m0");
 }
 
-__global__ __launch_bounds__(256, 2) void attn_mfma_kernel(
+// One of the 8 copy instructions of a wavefront's quarter tile: 64 lanes x 16 bytes, lane t lands at
+// LDS address dst + 1024*piece + 16*t.  src already includes the wavefront and lane offsets.
+__device__ inline void copy_piece_to_lds(const char *src, uint32_t dst, int piece) {
+    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off"
+                 :: "v"(src + piece * 1024), "s"(dst + piece * 1024) : "memory", "m0");
+}
+
+// exp2 of 8 scores of one accumulator (registers first..first+7 = 8 consecutive keys), rounded to
+// half for the second matrix product; the row sum accumulates the rounded values two at a time.
+__device__ inline void softmax_fragment(const f32x16 &sc, int first, float scale_log2, float m, f16x2 ones,
+                                        float &l, f16x8 &out) {
+#pragma unroll
+    for (int j = 0; j < 8; j += 2) {
+        f16x2 pp;
+        pp[0] = (_Float16)__builtin_amdgcn_exp2f(fmaf(sc[first + j], scale_log2, -m));
+        pp[1] = (_Float16)__builtin_amdgcn_exp2f(fmaf(sc[first + j + 1], scale_log2, -m));
+        l = __builtin_amdgcn_fdot2(pp, ones, l, false);
+        out[j] = pp[0];
+        out[j + 1] = pp[1];
+    }
+}
+
+// Largest score of each query column over the block's 128 keys (both lanes of a query agree).
+__device__ inline float block_row_max(const f32x16 (&sc)[4]) {
+    float mx = sc[0][0];
+#pragma unroll
+    for (int kg = 0; kg < 4; ++kg)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) mx = fmaxf(mx, sc[kg][i]);
+    return fmaxf(mx, __shfl_xor(mx, 32));
+}
+
+// A selected key block as the loop wants it: ring-slot tile index and which axes are clipped.
+//   bits 0..23 tile index (slot*nb + tile), bit 30 clipped in h, bit 31 clipped in w
+__device__ inline uint32_t pack_block(const KGeom &g, const KCache &c, int kb, int ph, int pw) {
+    const int f = kb / g.nb, kt = kb - f * g.nb;
+    const int kby = kt / g.tx, kbx = kt - kby * g.tx;
+    uint32_t v = (uint32_t)(slot_of_frame(c.start, g.cap, f) * g.nb + kt);
+    if (kby == g.ty - 1 && ph < g.th) v |= 1u << 30;
+    if (kbx == g.tx - 1 && pw < g.tw) v |= 1u << 31;
+    return v;
+}
+
+__global__ __launch_bounds__(512, 2) void attn_mfma_kernel(
     KGeom g, KCache c, const __bf16 *__restrict__ q, int64_t q_st, int64_t q_sh,
     const int32_t *__restrict__ sel_idx, const int32_t *__restrict__ sel_cnt,
     __bf16 *__restrict__ o, int64_t o_st, int64_t o_sh, float *__restrict__ lse,
-    float scale_log2, int total_items, int items_per_xcd) {
-    __shared__ __attribute__((aligned(16))) unsigned char k_lds[kTileBytes];
-    __shared__ __attribute__((aligned(16))) unsigned char v_lds[kTileBytes];
+    float scale_log2, int total_items, int pairs_per_xcd) {
+    __shared__ __attribute__((aligned(16))) unsigned char lds_all[2][2][kTileBytes];   // [group][K, V]
 
     // Workgroups are dealt to the 8 XCDs round-robin; give each XCD a contiguous run of work
     // items (same head, neighbouring tiles, both query frames) so that K/V tiles shared by
     // neighbouring windows are found in that XCD's L2.
     const int xcd = blockIdx.x & 7, idx = blockIdx.x >> 3;
-    const int item = xcd * items_per_xcd + idx;
-    if (item >= total_items) return;
-    const int head = item / (g.nb * g.q_frames);
-    const int rem = item - head * (g.nb * g.q_frames);
-    const int tile = rem / g.q_frames, fq = rem - tile * g.q_frames;
-    const int qb = fq * g.nb + tile;
-    const int by = tile / g.tx, bx = tile - by * g.tx;
-    const int qvh = min(g.th, g.H - by * g.th), qvw = min(g.tw, g.W - bx * g.tw);
+    const int total_pairs = (total_items + 1) >> 1;
+    const int pair = xcd * pairs_per_xcd + idx;
+    if (pair >= total_pairs) return;
 
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    const int ql = lane & 31, grp = lane >> 5;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int grp8 = __builtin_amdgcn_readfirstlane(tid >> 8);        // which group of 4 wavefronts
+    const int wave = __builtin_amdgcn_readfirstlane((tid >> 6) & 3);  // wavefront within the group
+    unsigned char *k_lds = lds_all[grp8][0], *v_lds = lds_all[grp8][1];
+    const int ql = lane & 31, half = lane >> 5;
     const int n_qb = g.q_frames * g.nb;
+
+    // this group's item, and how many blocks the other group has (the stage clock is shared)
+    auto item_row = [&](int item, int &head, int &qb) {
+        head = item / n_qb;
+        const int rem = item - head * n_qb;
+        const int tile = rem / g.q_frames, fq = rem - tile * g.q_frames;   // items ordered (head, tile, frame)
+        qb = fq * g.nb + tile;
+    };
+    const int item = 2 * pair + grp8, other = 2 * pair + (grp8 ^ 1);
+    const bool active = item < total_items;
+    int head = 0, qb = 0, cnt = 0, other_cnt = 0;
+    if (active) { item_row(item, head, qb); cnt = sel_cnt[(int64_t)head * n_qb + qb]; }
+    if (other < total_items) { int h2, q2; item_row(other, h2, q2); other_cnt = sel_cnt[(int64_t)h2 * n_qb + q2]; }
+    cnt = __builtin_amdgcn_readfirstlane(cnt);
+    other_cnt = __builtin_amdgcn_readfirstlane(other_cnt);
+    const int n_iter = max(cnt, other_cnt);
     const int64_t row = (int64_t)head * n_qb + qb;
-    const int cnt = sel_cnt[row];
     const int32_t *sel = sel_idx + row * g.topk;
 
-    // tile-token coordinates of keys `lane` and `lane + 64`, for the validity ballots of clipped tiles
-    const int kr0 = lane / g.tw, kc0 = lane - kr0 * g.tw;
-    const int kr1 = (lane + 64) / g.tw, kc1 = (lane + 64) - kr1 * g.tw;
+    const int fq = qb / g.nb, tile = qb - fq * g.nb;
+    const int by = tile / g.tx, bx = tile - by * g.tx;
+    const int qvh = min(g.th, g.H - by * g.th), qvw = min(g.tw, g.W - bx * g.tw);
+    const int ph = g.H - (g.ty - 1) * g.th, pw = g.W - (g.tx - 1) * g.tw;   // extent of clipped edge tiles
 
-    // ---- Q fragments (B operand of S^T = K Q^T): lane holds query ql of this wavefront, channels 16s+8grp..+8
+    // tile-token coordinates of keys `lane` and `lane + 64`, for the validity ballots of clipped tiles
+    // (four small numbers packed into one register; they are only unpacked for clipped tiles)
+    uint32_t key_rc;
+    {
+        const int kr0 = lane / g.tw, kc0 = lane - kr0 * g.tw;
+        const int kr1 = (lane + 64) / g.tw, kc1 = (lane + 64) - kr1 * g.tw;
+        key_rc = (uint32_t)kr0 | ((uint32_t)kc0 << 8) | ((uint32_t)kr1 << 16) | ((uint32_t)kc1 << 24);
+    }
+
+    // ---- Q fragments (B operand of S^T = K Q^T): lane holds query ql of this wavefront, channels 16s+8*half..+8
     const int tq = wave * 32 + ql;
     const int qr = tq / g.tw, qc = tq - qr * g.tw;
-    const bool q_valid = qr < qvh && qc < qvw;
+    const bool q_valid = active && qr < qvh && qc < qvw;
     const int64_t token = q_valid ? ((int64_t)fq * g.H + by * g.th + qr) * g.W + bx * g.tw + qc
                                   : ((int64_t)fq * g.H + by * g.th) * g.W + bx * g.tw;   // clamp padding rows
     bf16x8 bq[8];
     {
-        const __bf16 *qp = q + token * q_st + (int64_t)head * q_sh + grp * 8;
+        const __bf16 *qp = q + token * q_st + (int64_t)head * q_sh + half * 8;
 #pragma unroll
         for (int s = 0; s < 8; ++s) bq[s] = *(const bf16x8 *)(qp + s * 16);
     }
 
-    // selected ids of this row, 64 at a time, one per lane
-    int sel_chunk = lane < cnt ? sel[lane] : 0;
+    // selected blocks of this row, 64 at a time, one per lane, already turned into tile indices
+    uint32_t blk_chunk = lane < cnt ? pack_block(g, c, sel[lane], ph, pw) : 0u;
 
     // ---- per-lane LDS offsets
     // K operand: MFMA row m = ql reads key row pi(ql) of each 32-key group (bits 2,3 swapped)
     const int krow = (ql & 0x13) | ((ql & 4) << 1) | ((ql & 8) >> 1);
-    int k_off[8], v_off[8];
-#pragma unroll
-    for (int s = 0; s < 8; ++s) {
-        k_off[s] = krow * 256 + ((((s * 2 + grp) ^ (krow & 15))) << 4);    // + 8192 * key group
-        v_off[s] = ql * 256 + ((((s * 2 + grp) ^ (ql & 15))) << 4);        // + 8192 * channel group; s = chunk pair
-    }
+    // byte offset of the 16-byte chunk (2s + half) of this lane's row: row*256 + (((2s+half) ^ (row&15)) << 4)
+    //   = base ^ (s << 5) with base = row*256 + (((half ^ row) & 15) << 4): one XOR per read, two registers
+    const int k_base = krow * 256 + (((half ^ krow) & 15) << 4);     // + 8192 * key group
+    const int v_base = ql * 256 + (((half ^ ql) & 15) << 4);         // + 8192 * channel group
+    auto k_off = [&](int s) { return k_base ^ (s << 5); };
+    auto v_off = [&](int s) { return v_base ^ (s << 5); };
 
     f32x16 oacc[4];
 #pragma unroll
@@ -124,147 +201,208 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(
         for (int i = 0; i < 16; ++i) oacc[dt][i] = 0.f;
     float m_run = -__builtin_inff(), l_run = 0.f;
 
-    auto tile_ptr = [&](const void *base, int kb) {
-        const int f = kb / g.nb, kt = kb - f * g.nb;
-        const int slot = slot_of_frame(c.start, g.cap, f);
-        return (const char *)base + (((int64_t)head * g.cap + slot) * g.nb + kt) * (int64_t)kTileBytes;
-    };
+    const char *k_head = (const char *)c.k + (int64_t)head * g.cap * g.nb * kTileBytes;
+    const char *v_head = (const char *)c.v + (int64_t)head * g.cap * g.nb * kTileBytes;
+    auto tile_off = [](uint32_t blk) { return (int64_t)(blk & 0xffffffu) * kTileBytes; };
 
-    if (cnt > 0) {
-        const int kb0 = __builtin_amdgcn_readlane(sel_chunk, 0);
-        tile_to_lds(tile_ptr(c.k, kb0), k_lds, wave, lane);
-    }
+    uint32_t blk = __builtin_amdgcn_readlane(blk_chunk, 0);
+    __builtin_amdgcn_s_waitcnt(0x0F70);    // vmcnt(0), visible to the compiler: Q fragments and ids are in registers
+    if (cnt > 0) tile_to_lds(k_head + tile_off(blk), k_lds, wave, lane);
+    wait_vm0();
+    stage_barrier();                       // first K tiles of both groups are in LDS
+    if (grp8 == 1) { stage_barrier(); stage_barrier(); }   // group 1 runs two phases behind group 0
 
-    for (int it = 0; it < cnt; ++it) {
-        const int kb = __builtin_amdgcn_readlane(sel_chunk, it & 63);
-        // K tile of this iteration has landed (this wavefront's part), and after the barrier
-        // everyone's; the barrier also says that all wavefronts left the previous P*V, so the
-        // V buffer may be overwritten.
-        wait_tiles_and_barrier<0>();
-        tile_to_lds(tile_ptr(c.v, kb), v_lds, wave, lane);
+    f16x8 pfrag[8];                        // P^T fragments of the previous block: [key group*2 + k-step]
+    uint32_t blk_next = 0;
+    bool has_next = false;
+    float l_before = 0.f;
 
-        // ---- S^T = K Q^T : 4 key groups x 8 k-steps
-        f32x16 sacc[4];
+    // Four phases per block, each ending in a workgroup barrier:
+    //   P1  PV(i-1)            matrix     P3  softmax(i), key groups 0,1   vector
+    //   P2  QK(i)              matrix     P4  softmax(i), key groups 2,3   vector
+    // Group 1 is two phases behind, so every SIMD always holds one wavefront in a matrix phase and
+    // one in a vector phase.  Tile copies: V(i) is issued during P2(i) and needed at P1(i+1);
+    // K(i+1) is issued during P3(i) and needed at P2(i+1): three phases of lead each.  The eight
+    // copy instructions of a tile are spread through the phase because each one can hold the
+    // issuing wavefront while the memory pipeline accepts it.
+    for (int it = 0; it <= n_iter; ++it) {
+        const bool pv_on = it >= 1 && it - 1 < cnt;   // wavefront-uniform
+        const bool on = it < cnt;
+        f32x16 sacc[4];                    // S^T of this block: produced in P2, consumed in P3 and P4
+
+        // ================= P1: O^T += V^T P^T of the previous block (8 k-steps x 4 channel groups) ====
+        if (pv_on) {
+            __builtin_amdgcn_s_setprio(2);
+            f16x8 va[kRing];
 #pragma unroll
-        for (int kg = 0; kg < 4; ++kg) {
+            for (int n = 0; n < kAhead; ++n) va[n % kRing] = *(const f16x8 *)(v_lds + (n & 3) * 8192 + v_off(n >> 2));
 #pragma unroll
-            for (int i = 0; i < 16; ++i) sacc[kg][i] = 0.f;
+            for (int n = 0; n < 32; ++n) {
+                const int ks = n >> 2, dt = n & 3;
+                if (n + kAhead < 32)
+                    va[(n + kAhead) % kRing] = *(const f16x8 *)(v_lds + ((n + kAhead) & 3) * 8192 + v_off((n + kAhead) >> 2));
+                oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(va[n % kRing], pfrag[ks], oacc[dt], 0, 0, 0);
+            }
+            __builtin_amdgcn_sched_group_barrier(0x100, kAhead, 0);
 #pragma unroll
-            for (int s = 0; s < 8; ++s) {
-                const bf16x8 a = *(const bf16x8 *)(k_lds + kg * 8192 + k_off[s]);
-                sacc[kg] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bq[s], sacc[kg], 0, 0, 0);
+            for (int i = 0; i < 32 - kAhead; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            }
+            __builtin_amdgcn_sched_group_barrier(0x008, kAhead, 0);
+            __builtin_amdgcn_s_setprio(0);
+        }
+        if (on) wait_vm0();                // K(i) (this wavefront's part) has landed
+        __builtin_amdgcn_sched_barrier(0);
+        stage_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+
+        // ================= P2: S^T = K Q^T (4 key groups x 8 k-steps); V(i) copy issued alongside =====
+        if (on) {
+            blk = it == 0 ? blk : blk_next;
+            __builtin_amdgcn_s_setprio(2);
+            const char *vsrc = v_head + tile_off(blk) + wave * 8192 + lane * 16;
+            const uint32_t vdst = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)((LCSA_LDS unsigned char *)v_lds) + wave * 8192);
+            bf16x8 ka[kRing];
+#pragma unroll
+            for (int n = 0; n < kAhead; ++n) ka[n % kRing] = *(const bf16x8 *)(k_lds + (n >> 3) * 8192 + k_off(n & 7));
+            __builtin_amdgcn_sched_group_barrier(0x100, kAhead, 0);
+#pragma unroll
+            for (int n = 0; n < 32; ++n) {
+                const int kg = n >> 3, s = n & 7;
+                if (s == 0) {
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) sacc[kg][i] = 0.f;
+                }
+                if ((n & 3) == 0) copy_piece_to_lds(vsrc, vdst, n >> 2);     // one of the 8 copy instructions per 4 MFMAs
+                if (n + kAhead < 32) {
+                    ka[(n + kAhead) % kRing] = *(const bf16x8 *)(k_lds + ((n + kAhead) >> 3) * 8192 + k_off((n + kAhead) & 7));
+                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                }
+                sacc[kg] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[n % kRing], bq[s], sacc[kg], 0, 0, 0);
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            }
+            __builtin_amdgcn_s_setprio(0);
+            // next block; every 64 iterations the per-lane chunk is refilled (the read of the fresh
+            // value sits inside the branch so that the wait for that load does too)
+            has_next = it + 1 < cnt;
+            if (has_next) {
+                if (((it + 1) & 63) == 0) {
+                    blk_chunk = (it + 1 + lane) < cnt ? pack_block(g, c, sel[it + 1 + lane], ph, pw) : 0u;
+                    blk_next = __builtin_amdgcn_readlane(blk_chunk, 0);
+                } else {
+                    blk_next = __builtin_amdgcn_readlane(blk_chunk, (it + 1) & 63);
+                }
             }
         }
+        __builtin_amdgcn_sched_barrier(0);
+        stage_barrier();
+        __builtin_amdgcn_sched_barrier(0);
 
-        // id of the next block; every 64 iterations the per-lane chunk of ids is refilled
-        // (the read of the fresh value sits inside the branch so that the wait for that load
-        // does too, instead of draining the tile copies on every iteration)
-        int kb_next = -1;
-        if (it + 1 < cnt) {
-            if (((it + 1) & 63) == 0) {
-                sel_chunk = (it + 1 + lane) < cnt ? sel[it + 1 + lane] : 0;
-                kb_next = __builtin_amdgcn_readlane(sel_chunk, 0);
-            } else {
-                kb_next = __builtin_amdgcn_readlane(sel_chunk, (it + 1) & 63);
-            }
-        }
-        // all wavefronts are done reading K: stream in the next K tile behind the V tile
-        lds_barrier();
-        if (kb_next >= 0) tile_to_lds(tile_ptr(c.k, kb_next), k_lds, wave, lane);
+        // ================= P3: online softmax, first half; K(i+1) copy issued alongside ===============
+        const char *ksrc = k_head + tile_off(blk_next) + wave * 8192 + lane * 16;
+        const uint32_t kdst = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)((LCSA_LDS unsigned char *)k_lds) + wave * 8192);
+        const f16x2 ones = {(_Float16)1.f, (_Float16)1.f};
+        if (on) {
+            // everyone in the group is done reading K: the next K tile may overwrite it
+            if (has_next) { copy_piece_to_lds(ksrc, kdst, 0); copy_piece_to_lds(ksrc, kdst, 1); }
 
-        // ---- padding keys of clipped tiles get weight exactly zero
-        {
-            const int f = kb / g.nb, kt = kb - f * g.nb, kby = kt / g.tx, kbx = kt - kby * g.tx;
-            const int kvh = min(g.th, g.H - kby * g.th), kvw = min(g.tw, g.W - kbx * g.tw);
-            if (kvh < g.th || kvw < g.tw) {                 // wavefront-uniform
+            // padding keys of clipped tiles get weight exactly zero
+            if (blk >> 30) {
+                const int kvh = (blk & (1u << 30)) ? ph : g.th, kvw = (blk & (1u << 31)) ? pw : g.tw;
+                const int kr0 = key_rc & 255, kc0 = (key_rc >> 8) & 255, kr1 = (key_rc >> 16) & 255, kc1 = key_rc >> 24;
                 const uint64_t b0 = __ballot(kr0 < kvh && kc0 < kvw);   // keys 0..63
                 const uint64_t b1 = __ballot(kr1 < kvh && kc1 < kvw);   // keys 64..127
                 const uint32_t key_ok[4] = {(uint32_t)b0, (uint32_t)(b0 >> 32), (uint32_t)b1, (uint32_t)(b1 >> 32)};
 #pragma unroll
                 for (int kg = 0; kg < 4; ++kg) {
-                    // accumulator register i of key group kg is key kg*32 + (i>>3)*16 + grp*8 + (i&7)
-                    const uint32_t mbits = key_ok[kg] >> (grp * 8);
+                    // accumulator register i of key group kg is key kg*32 + (i>>3)*16 + half*8 + (i&7)
+                    const uint32_t mbits = key_ok[kg] >> (half * 8);
 #pragma unroll
                     for (int i = 0; i < 16; ++i)
                         if (!((mbits >> ((i >> 3) * 16 + (i & 7))) & 1u)) sacc[kg][i] = -__builtin_inff();
                 }
             }
+
+            // Reference point of the exponentials.  Any per-query reference gives the same softmax after
+            // the final normalisation; it only has to keep 2^(score - reference) inside half's range.
+            // The first block sets it to its exact row maximum; later blocks reuse it without looking
+            // for their maximum (which would cost a pass over all scores) and are checked afterwards:
+            // see the end of P4.
+            if (it == 0) m_run = block_row_max(sacc) * scale_log2;
+            if (has_next) { copy_piece_to_lds(ksrc, kdst, 2); copy_piece_to_lds(ksrc, kdst, 3); }
+            l_before = l_run;
+            // probabilities -> half; the row sum is taken over the rounded values (what the matrix
+            // product will use) with v_dot2_f32_f16, two per instruction
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) {
+                if (has_next && ks == 2) { copy_piece_to_lds(ksrc, kdst, 4); copy_piece_to_lds(ksrc, kdst, 5); }
+                softmax_fragment(sacc[ks >> 1], (ks & 1) * 8, scale_log2, m_run, ones, l_run, pfrag[ks]);
+                __builtin_amdgcn_sched_barrier(0);
+            }
         }
-
-        // ---- online softmax over this block's 128 keys, per query column
-        float mx = sacc[0][0];
-#pragma unroll
-        for (int kg = 0; kg < 4; ++kg)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) mx = fmaxf(mx, sacc[kg][i]);
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
-        const float m_new = fmaxf(m_run, mx * scale_log2);
-        const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-        float psum = 0.f;
-#pragma unroll
-        for (int kg = 0; kg < 4; ++kg)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const float p = __builtin_amdgcn_exp2f(fmaf(sacc[kg][i], scale_log2, -m_new));
-                sacc[kg][i] = p;
-                psum += p;
-            }
-        l_run = l_run * alpha + psum;
-        m_run = m_new;
-#pragma unroll
-        for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) oacc[dt][i] *= alpha;
-
-        // V tile has landed (the 8 newer loads in flight are the next K tile, if any)
         __builtin_amdgcn_sched_barrier(0);
-        if (kb_next >= 0) wait_tiles_and_barrier<8>();
-        else wait_tiles_and_barrier<0>();
+        stage_barrier();
         __builtin_amdgcn_sched_barrier(0);
 
-        // ---- O^T += V^T P^T : 8 k-steps of 16 keys x 4 channel groups
+        // ================= P4: online softmax, second half =============================================
+        if (on) {
+            if (has_next) { copy_piece_to_lds(ksrc, kdst, 6); copy_piece_to_lds(ksrc, kdst, 7); }
 #pragma unroll
-        for (int kg = 0; kg < 4; ++kg)
-#pragma unroll
-            for (int s2 = 0; s2 < 2; ++s2) {
-                f16x8 pb;
-#pragma unroll
-                for (int j = 0; j < 8; ++j) pb[j] = (_Float16)sacc[kg][s2 * 8 + j];
-#pragma unroll
-                for (int dt = 0; dt < 4; ++dt) {
-                    const f16x8 a = *(const f16x8 *)(v_lds + dt * 8192 + v_off[kg * 2 + s2]);
-                    oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, pb, oacc[dt], 0, 0, 0);
-                }
+            for (int ks = 4; ks < 8; ++ks) {
+                softmax_fragment(sacc[ks >> 1], (ks & 1) * 8, scale_log2, m_run, ones, l_run, pfrag[ks]);
+                __builtin_amdgcn_sched_barrier(0);
             }
+            // Check of the reference: this lane's 64 probabilities sum to less than 2^14, hence none of them
+            // left half's range.  Otherwise (a block whose scores tower over everything seen before, or
+            // non-finite input) redo the block against its exact maximum, rescaling the running sums.
+            if (__ballot(!(l_run - l_before < 16384.f))) {
+                const float m_new = fmaxf(m_run, block_row_max(sacc) * scale_log2);
+                const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+                l_run = l_before * alpha;
+#pragma unroll
+                for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) oacc[dt][i] *= alpha;
+                m_run = m_new;
+#pragma unroll
+                for (int ks = 0; ks < 8; ++ks)
+                    softmax_fragment(sacc[ks >> 1], (ks & 1) * 8, scale_log2, m_run, ones, l_run, pfrag[ks]);
+            }
+            // V(i) has landed (the 8 newer copies in flight are the next K tile, if any)
+            if (has_next) wait_vm8(); else wait_vm0();
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        stage_barrier();
+        __builtin_amdgcn_sched_barrier(0);
     }
+    if (grp8 == 0) { stage_barrier(); stage_barrier(); }   // matches group 1's two extra barriers at the start
 
-    // ---- epilogue: normalise, transpose through LDS, store rows of 256 bytes
-    __syncthreads();                                        // all P*V reads of LDS are done
+    // ---- epilogue: normalise, transpose through this wavefront's own 8 KB of LDS, store 256-byte rows.
+    // No LDS reads of other wavefronts are outstanding: the last stage ended in a barrier.
+    if (!active) return;
     const float l_tot = l_run + __shfl_xor(l_run, 32);
     const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
-    {
-        // lane owns query row tq; accumulator register i of channel group dt is channel
-        // dt*32 + (i>>2)*8 + grp*4 + (i&3): 4 consecutive channels = 8 bytes
+    // lane owns query row tq; accumulator register i of channel group dt is channel
+    // dt*32 + (i>>2)*8 + half*4 + (i&3): 4 consecutive channels = 8 bytes
 #pragma unroll
-        for (int dt = 0; dt < 4; ++dt)
+    for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
-            for (int i4 = 0; i4 < 4; ++i4) {
-                typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
-                bf16x4 w;
+        for (int i4 = 0; i4 < 4; ++i4) {
+            bf16x4 w;
 #pragma unroll
-                for (int j = 0; j < 4; ++j) w[j] = (__bf16)(oacc[dt][i4 * 4 + j] * inv);
-                const int chunk = dt * 4 + i4;
-                *(bf16x4 *)(k_lds + tq * 256 + ((chunk ^ (tq & 15)) << 4) + grp * 8) = w;
-            }
-    }
-    if (lse && grp == 0 && q_valid)
+            for (int j = 0; j < 4; ++j) w[j] = (__bf16)(oacc[dt][i4 * 4 + j] * inv);
+            const int chunk = dt * 4 + i4;
+            *(bf16x4 *)(k_lds + tq * 256 + ((chunk ^ (tq & 15)) << 4) + half * 8) = w;
+        }
+    if (lse && half == 0 && q_valid)
         lse[token * g.heads + head] = l_tot > 0.f ? (m_run + __builtin_amdgcn_logf(l_tot)) * kLn2 : -__builtin_inff();
-    __syncthreads();
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");     // rows written by this wavefront are read by it only
     {
-        const int rg = tid >> 4, j = tid & 15;
+        const int rg = lane >> 4, j = lane & 15;            // 4 rows per pass, 16 lanes x 16 bytes per row
 #pragma unroll
         for (int itr = 0; itr < 8; ++itr) {
-            const int t = rg + 16 * itr;
+            const int t = wave * 32 + rg + 4 * itr;
             const int r = t / g.tw, cc = t - r * g.tw;
             if (r < qvh && cc < qvw) {
                 const int64_t tok = ((int64_t)fq * g.H + by * g.th + r) * g.W + bx * g.tw + cc;
@@ -281,8 +419,9 @@ hipError_t launch_attn_mfma(const KGeom &g, const KCache &c, const void *q, int6
                             const int32_t *sel_idx, const int32_t *sel_cnt,
                             void *o, int64_t o_st, int64_t o_sh, float *lse, float scale, hipStream_t stream) {
     const int total = g.heads * g.nb * g.q_frames;
-    const int per_xcd = (total + 7) / 8;
-    attn_mfma_kernel<<<dim3(per_xcd * 8), 256, 0, stream>>>(g, c, (const __bf16 *)q, q_st, q_sh, sel_idx, sel_cnt,
+    const int pairs = (total + 1) / 2;
+    const int per_xcd = (pairs + 7) / 8;
+    attn_mfma_kernel<<<dim3(per_xcd * 8), 512, 0, stream>>>(g, c, (const __bf16 *)q, q_st, q_sh, sel_idx, sel_cnt,
                                                             (__bf16 *)o, o_st, o_sh, lse, scale * kLog2e,
                                                             total, per_xcd);
     return hipGetLastError();

@@ -247,3 +247,28 @@ def test_launch_is_deterministic():
         outs.append((sel_idx.clone(), B.lcsa_sparse_attn_fwd(p.g, qd, p.cache, sel_idx, sel_cnt).clone()))
     torch.cuda.synchronize()
     assert torch.equal(outs[0][0], outs[1][0]) and torch.equal(outs[0][1].view(torch.int16), outs[1][1].view(torch.int16))
+
+
+def test_late_dominant_block_redoes_softmax_reference():
+    """Keys of the newest frame score ~2^16 times higher (in the exp2 domain) than anything before: the
+    kernel's lazily kept softmax reference must be caught by its range check and redone exactly."""
+    w, g, og, mk, n = _closed_form_setup(heads=2)
+    g2, og2 = geoms(w, topk=12, radius=-1)
+    cache = B.lcsa_cache_init(g2)
+    rng = np.random.default_rng(21)
+    K = wl.round_to_bf16((0.1 * rng.standard_normal((6 * n, 2, 128))).astype(np.float32))
+    V = mk(6)
+    q = wl.round_to_bf16((4.0 + 0.05 * rng.standard_normal((2 * n, 2, 128))).astype(np.float32))
+    K[5 * n:] += 0.25            # newest frame: q.k ~ 128 -> log2-domain jump of ~16 over the earlier blocks
+    K = wl.round_to_bf16(K)
+    B.lcsa_kv_cache_append(cache, to_device(K, "bf16"), to_device(V, "bf16"), 6)
+    qd = to_device(q, "bf16")
+    sel_idx, sel_cnt, _ = B.lcsa_select_blocks(g2, B.lcsa_pool_blocks(g2, qd, 2), cache)
+    lse = torch.empty(qd.shape[0], 2, dtype=torch.float32, device="cuda")
+    o = B.lcsa_sparse_attn_fwd(g2, qd, cache, sel_idx, sel_cnt, lse=lse)
+    torch.cuda.synchronize()
+    s_idx, s_cnt = sel_idx.cpu().numpy(), sel_cnt.cpu().numpy()
+    assert (s_idx[..., -1] >= 5 * g2.nb).all() and (s_idx[..., 0] < 5 * g2.nb).all()   # old blocks first, dominant ones last
+    check_outputs(o, q, K, V, og2, 6, s_idx, s_cnt, None)
+    _, want_lse = oracle.attend(q, K, V, og2, 6, s_idx, s_cnt, with_lse=True)
+    np.testing.assert_allclose(lse.cpu().numpy(), want_lse, rtol=0, atol=5e-3)
