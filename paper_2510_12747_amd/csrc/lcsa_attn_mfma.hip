@@ -42,8 +42,9 @@ typedef __attribute__((ext_vector_type(2))) _Float16 f16x2;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 
 constexpr int kTileBytes = 128 * 256;
-constexpr int kAhead = 6;            // operand fragments in flight ahead of the matrix instruction using them
+constexpr int kAhead = 4;            // operand fragments in flight ahead of the matrix instruction using them
 constexpr int kRing = kAhead + 1;
+constexpr int kSplit = 4;            // softmax fragments (of 8) done in the first vector phase; the rest in the second
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 
@@ -79,17 +80,17 @@ __device__ inline void copy_piece_to_lds(const char *src, uint32_t dst, int piec
 }
 
 // exp2 of 8 scores of one accumulator (registers first..first+7 = 8 consecutive keys), rounded to
-// half for the second matrix product; the row sum accumulates the rounded values two at a time.
-__device__ inline void softmax_fragment(const f32x16 &sc, int first, float scale_log2, float m, f16x2 ones,
-                                        float &l, f16x8 &out) {
+// half for the second matrix product; the row sum is kept in float.  (Plain adds on purpose: the
+// dot-product instructions v_dot2* run on the matrix pipeline and do not overlap with MFMAs of the
+// other wavefront on the SIMD, ordinary vector instructions do.)
+__device__ inline void softmax_fragment(const f32x16 &sc, int first, float scale_log2, float m, float &l, f16x8 &out) {
 #pragma unroll
     for (int j = 0; j < 8; j += 2) {
-        f16x2 pp;
-        pp[0] = (_Float16)__builtin_amdgcn_exp2f(fmaf(sc[first + j], scale_log2, -m));
-        pp[1] = (_Float16)__builtin_amdgcn_exp2f(fmaf(sc[first + j + 1], scale_log2, -m));
-        l = __builtin_amdgcn_fdot2(pp, ones, l, false);
-        out[j] = pp[0];
-        out[j + 1] = pp[1];
+        const float p0 = __builtin_amdgcn_exp2f(fmaf(sc[first + j], scale_log2, -m));
+        const float p1 = __builtin_amdgcn_exp2f(fmaf(sc[first + j + 1], scale_log2, -m));
+        l += p0 + p1;
+        out[j] = (_Float16)p0;
+        out[j + 1] = (_Float16)p1;
     }
 }
 
@@ -218,11 +219,11 @@ __global__ __launch_bounds__(512, 2) void attn_mfma_kernel(
     float l_before = 0.f;
 
     // Four phases per block, each ending in a workgroup barrier:
-    //   P1  PV(i-1)            matrix     P3  softmax(i), key groups 0,1   vector
-    //   P2  QK(i)              matrix     P4  softmax(i), key groups 2,3   vector
+    //   P1  PV(i-1)            matrix     P3  softmax(i), first fragments   vector
+    //   P2  QK(i)              matrix     P4  softmax(i), the rest + check  vector
     // Group 1 is two phases behind, so every SIMD always holds one wavefront in a matrix phase and
     // one in a vector phase.  Tile copies: V(i) is issued during P2(i) and needed at P1(i+1);
-    // K(i+1) is issued during P3(i) and needed at P2(i+1): three phases of lead each.  The eight
+    // K(i+1) is issued during P3(i) and P4(i) and needed at P2(i+1): two to three phases of lead.  The eight
     // copy instructions of a tile are spread through the phase because each one can hold the
     // issuing wavefront while the memory pipeline accepts it.
     for (int it = 0; it <= n_iter; ++it) {
@@ -302,7 +303,6 @@ __global__ __launch_bounds__(512, 2) void attn_mfma_kernel(
         // ================= P3: online softmax, first half; K(i+1) copy issued alongside ===============
         const char *ksrc = k_head + tile_off(blk_next) + wave * 8192 + lane * 16;
         const uint32_t kdst = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)((LCSA_LDS unsigned char *)k_lds) + wave * 8192);
-        const f16x2 ones = {(_Float16)1.f, (_Float16)1.f};
         if (on) {
             // everyone in the group is done reading K: the next K tile may overwrite it
             if (has_next) { copy_piece_to_lds(ksrc, kdst, 0); copy_piece_to_lds(ksrc, kdst, 1); }
@@ -332,12 +332,10 @@ __global__ __launch_bounds__(512, 2) void attn_mfma_kernel(
             if (it == 0) m_run = block_row_max(sacc) * scale_log2;
             if (has_next) { copy_piece_to_lds(ksrc, kdst, 2); copy_piece_to_lds(ksrc, kdst, 3); }
             l_before = l_run;
-            // probabilities -> half; the row sum is taken over the rounded values (what the matrix
-            // product will use) with v_dot2_f32_f16, two per instruction
+            // probabilities -> half for the matrix product; row sum in float
 #pragma unroll
-            for (int ks = 0; ks < 4; ++ks) {
-                if (has_next && ks == 2) { copy_piece_to_lds(ksrc, kdst, 4); copy_piece_to_lds(ksrc, kdst, 5); }
-                softmax_fragment(sacc[ks >> 1], (ks & 1) * 8, scale_log2, m_run, ones, l_run, pfrag[ks]);
+            for (int ks = 0; ks < kSplit; ++ks) {
+                softmax_fragment(sacc[ks >> 1], (ks & 1) * 8, scale_log2, m_run, l_run, pfrag[ks]);
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
@@ -347,10 +345,11 @@ __global__ __launch_bounds__(512, 2) void attn_mfma_kernel(
 
         // ================= P4: online softmax, second half =============================================
         if (on) {
-            if (has_next) { copy_piece_to_lds(ksrc, kdst, 6); copy_piece_to_lds(ksrc, kdst, 7); }
+            if (has_next) { copy_piece_to_lds(ksrc, kdst, 4); copy_piece_to_lds(ksrc, kdst, 5); }
 #pragma unroll
-            for (int ks = 4; ks < 8; ++ks) {
-                softmax_fragment(sacc[ks >> 1], (ks & 1) * 8, scale_log2, m_run, ones, l_run, pfrag[ks]);
+            for (int ks = kSplit; ks < 8; ++ks) {
+                if (has_next && ks == 5) { copy_piece_to_lds(ksrc, kdst, 6); copy_piece_to_lds(ksrc, kdst, 7); }
+                softmax_fragment(sacc[ks >> 1], (ks & 1) * 8, scale_log2, m_run, l_run, pfrag[ks]);
                 __builtin_amdgcn_sched_barrier(0);
             }
             // Check of the reference: this lane's 64 probabilities sum to less than 2^14, hence none of them
@@ -367,7 +366,7 @@ __global__ __launch_bounds__(512, 2) void attn_mfma_kernel(
                 m_run = m_new;
 #pragma unroll
                 for (int ks = 0; ks < 8; ++ks)
-                    softmax_fragment(sacc[ks >> 1], (ks & 1) * 8, scale_log2, m_run, ones, l_run, pfrag[ks]);
+                    softmax_fragment(sacc[ks >> 1], (ks & 1) * 8, scale_log2, m_run, l_run, pfrag[ks]);
             }
             // V(i) has landed (the 8 newer copies in flight are the next K tile, if any)
             if (has_next) wait_vm8(); else wait_vm0();
