@@ -26,6 +26,11 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 / fp16 matrix peak
 PEAK_HBM_GBS = 8000.0
 
+# HBM-side bytes per attention launch (L2 <-> fabric), from the rocprofv3 --pmc passes summarised in
+# profiles/hot_path_paper_scale_pmc.txt: FETCH_SIZE x 2.0 (factor from a 1 GiB copy) + WRITE_SIZE x 1.0, in bytes.
+# Counters cannot be read from inside this script; the figure is only quoted for the workload it was taken on.
+ATTN_TRAFFIC_BYTES = {("paper", 32): 296.4e6 + 29.5e6}
+
 WORKLOAD_TEXT = {
     "paper": "paper-scale 768x1408: 48x88 tokens/frame, 2 query + 4 cached frames, 8x16 tiles, radius 24, top-k 32, 30 layer calls",
     "small": "small-video 384x704: 24x44 tokens/frame, 2 query + 4 cached frames, 8x16 tiles, radius 16, top-k 16",
@@ -193,7 +198,7 @@ def main() -> int:
                     "pool_blocks": round(pool_bytes / (brk[1] * 1e-3) / 1e9, 1)},
         "roofline": {"kernel": "attn_mfma_kernel", "bound": "mfma", "achieved": round(achieved, 2),
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
-                     "traffic": None,
+                     "traffic": ATTN_TRAFFIC_BYTES.get((args.workload, topk)),
                      "flop_per_launch_useful": useful_flop, "flop_per_launch_issued": issued_flop,
                      "issued_tflops": round(issued_flop / (attn_avg_ms * 1e-3) / 1e12, 2),
                      "avg_launch_ms": round(attn_avg_ms, 5), "min_launch_ms": round(float(attn_ms.min()), 5)},
