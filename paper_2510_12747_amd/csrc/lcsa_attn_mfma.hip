@@ -60,23 +60,19 @@ __device__ inline void stage_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts
 __device__ inline void wait_vm0() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 __device__ inline void wait_vm8() { asm volatile("s_waitcnt vmcnt(8)" ::: "memory"); }
 
-// Each wavefront of a group copies its quarter (8 KB) of a 32 KB tile image: 8 loads of
-// 64 lanes x 16 bytes; lane t of a load lands at LDS address M0 + 16*t.
-__device__ inline void tile_to_lds(const char *gsrc, unsigned char *lds, int wave, int lane) {
-    const char *gp = gsrc + wave * 8192 + lane * 16;
-    uint32_t dst = (uint32_t)(uintptr_t)((LCSA_LDS unsigned char *)lds) + wave * 8192;
-    dst = __builtin_amdgcn_readfirstlane(dst);
-#pragma unroll
-    for (int i = 0; i < 8; ++i)
-        asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off"
-                     :: "v"(gp + i * 1024), "s"(dst + i * 1024) : "memory", "m0");
-}
-
 // One of the 8 copy instructions of a wavefront's quarter tile: 64 lanes x 16 bytes, lane t lands at
-// LDS address dst + 1024*piece + 16*t.  src already includes the wavefront and lane offsets.
-__device__ inline void copy_piece_to_lds(const char *src, uint32_t dst, int piece) {
-    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off"
-                 :: "v"(src + piece * 1024), "s"(dst + piece * 1024) : "memory", "m0");
+// LDS address dst + 1024*piece + 16*t (M0 + immediate + 16*t).  The source is scalar base (the tile, wavefront-uniform) +
+// per-lane byte offset `voff` (wavefront quarter + 16*lane, loop invariant) + an immediate, so the
+// copies cost no vector arithmetic.
+__device__ inline void copy_piece_to_lds(const char *tile, uint32_t voff, uint32_t dst, int piece) {
+    const char *base = tile + (piece >> 2) * 4096;        // immediates reach 4095 bytes
+    const uint32_t m0v = dst + (piece >> 2) * 4096;        // the immediate offset is added to the LDS address too
+    switch (piece & 3) {
+    case 0: asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" :: "v"(voff), "s"(base), "s"(m0v) : "memory", "m0"); break;
+    case 1: asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1 offset:1024" :: "v"(voff), "s"(base), "s"(m0v) : "memory", "m0"); break;
+    case 2: asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1 offset:2048" :: "v"(voff), "s"(base), "s"(m0v) : "memory", "m0"); break;
+    default: asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1 offset:3072" :: "v"(voff), "s"(base), "s"(m0v) : "memory", "m0"); break;
+    }
 }
 
 // exp2 of 8 scores of one accumulator (registers first..first+7 = 8 consecutive keys), rounded to
@@ -206,9 +202,14 @@ __global__ __launch_bounds__(512, 2) void attn_mfma_kernel(
     const char *v_head = (const char *)c.v + (int64_t)head * g.cap * g.nb * kTileBytes;
     auto tile_off = [](uint32_t blk) { return (int64_t)(blk & 0xffffffu) * kTileBytes; };
 
+    const uint32_t copy_voff = wave * 8192 + lane * 16;     // this lane's byte offset inside any tile image
     uint32_t blk = __builtin_amdgcn_readlane(blk_chunk, 0);
     __builtin_amdgcn_s_waitcnt(0x0F70);    // vmcnt(0), visible to the compiler: Q fragments and ids are in registers
-    if (cnt > 0) tile_to_lds(k_head + tile_off(blk), k_lds, wave, lane);
+    if (cnt > 0) {
+        const uint32_t kdst0 = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)((LCSA_LDS unsigned char *)k_lds) + wave * 8192);
+#pragma unroll
+        for (int piece = 0; piece < 8; ++piece) copy_piece_to_lds(k_head + tile_off(blk), copy_voff, kdst0, piece);
+    }
     wait_vm0();
     stage_barrier();                       // first K tiles of both groups are in LDS
     if (grp8 == 1) { stage_barrier(); stage_barrier(); }   // group 1 runs two phases behind group 0
@@ -262,7 +263,7 @@ __global__ __launch_bounds__(512, 2) void attn_mfma_kernel(
         if (on) {
             blk = it == 0 ? blk : blk_next;
             __builtin_amdgcn_s_setprio(2);
-            const char *vsrc = v_head + tile_off(blk) + wave * 8192 + lane * 16;
+            const char *vsrc = v_head + tile_off(blk);
             const uint32_t vdst = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)((LCSA_LDS unsigned char *)v_lds) + wave * 8192);
             bf16x8 ka[kRing];
 #pragma unroll
@@ -275,7 +276,7 @@ __global__ __launch_bounds__(512, 2) void attn_mfma_kernel(
 #pragma unroll
                     for (int i = 0; i < 16; ++i) sacc[kg][i] = 0.f;
                 }
-                if ((n & 3) == 0) copy_piece_to_lds(vsrc, vdst, n >> 2);     // one of the 8 copy instructions per 4 MFMAs
+                if ((n & 3) == 0) copy_piece_to_lds(vsrc, copy_voff, vdst, n >> 2);     // one of the 8 copy instructions per 4 MFMAs
                 if (n + kAhead < 32) {
                     ka[(n + kAhead) % kRing] = *(const bf16x8 *)(k_lds + ((n + kAhead) >> 3) * 8192 + k_off((n + kAhead) & 7));
                     __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
@@ -301,11 +302,11 @@ __global__ __launch_bounds__(512, 2) void attn_mfma_kernel(
         __builtin_amdgcn_sched_barrier(0);
 
         // ================= P3: online softmax, first half; K(i+1) copy issued alongside ===============
-        const char *ksrc = k_head + tile_off(blk_next) + wave * 8192 + lane * 16;
+        const char *ksrc = k_head + tile_off(blk_next);
         const uint32_t kdst = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)((LCSA_LDS unsigned char *)k_lds) + wave * 8192);
         if (on) {
             // everyone in the group is done reading K: the next K tile may overwrite it
-            if (has_next) { copy_piece_to_lds(ksrc, kdst, 0); copy_piece_to_lds(ksrc, kdst, 1); }
+            if (has_next) { copy_piece_to_lds(ksrc, copy_voff, kdst, 0); copy_piece_to_lds(ksrc, copy_voff, kdst, 1); }
 
             // padding keys of clipped tiles get weight exactly zero
             if (blk >> 30) {
@@ -330,7 +331,7 @@ __global__ __launch_bounds__(512, 2) void attn_mfma_kernel(
             // for their maximum (which would cost a pass over all scores) and are checked afterwards:
             // see the end of P4.
             if (it == 0) m_run = block_row_max(sacc) * scale_log2;
-            if (has_next) { copy_piece_to_lds(ksrc, kdst, 2); copy_piece_to_lds(ksrc, kdst, 3); }
+            if (has_next) { copy_piece_to_lds(ksrc, copy_voff, kdst, 2); copy_piece_to_lds(ksrc, copy_voff, kdst, 3); }
             l_before = l_run;
             // probabilities -> half for the matrix product; row sum in float
 #pragma unroll
@@ -345,10 +346,10 @@ __global__ __launch_bounds__(512, 2) void attn_mfma_kernel(
 
         // ================= P4: online softmax, second half =============================================
         if (on) {
-            if (has_next) { copy_piece_to_lds(ksrc, kdst, 4); copy_piece_to_lds(ksrc, kdst, 5); }
+            if (has_next) { copy_piece_to_lds(ksrc, copy_voff, kdst, 4); copy_piece_to_lds(ksrc, copy_voff, kdst, 5); }
 #pragma unroll
             for (int ks = kSplit; ks < 8; ++ks) {
-                if (has_next && ks == 5) { copy_piece_to_lds(ksrc, kdst, 6); copy_piece_to_lds(ksrc, kdst, 7); }
+                if (has_next && ks == 5) { copy_piece_to_lds(ksrc, copy_voff, kdst, 6); copy_piece_to_lds(ksrc, copy_voff, kdst, 7); }
                 softmax_fragment(sacc[ks >> 1], (ks & 1) * 8, scale_log2, m_run, l_run, pfrag[ks]);
                 __builtin_amdgcn_sched_barrier(0);
             }

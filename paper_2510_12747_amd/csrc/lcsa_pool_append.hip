@@ -76,13 +76,23 @@ __global__ __launch_bounds__(kThreads) void pool_kernel(KGeom g, const char *x, 
 #pragma unroll
     for (int e = 0; e < VEC; ++e) acc[e] = 0.f;
     if (active) {
-        for (int tok = rg; tok < g.bt; tok += rows_par) {
-            int r = tok / g.tw, c = tok - r * g.tw;
-            if (r < t.vh && c < t.vw) {
-                int64_t token = ((int64_t)t.frame * g.H + t.by * g.th + r) * g.W + t.bx * g.tw + c;
-                uint4 u = *(const uint4 *)(x + (token * st + (int64_t)head * sh + j * VEC) * ELT);
+        // 8 token rows per lane are requested before any is consumed, so the loads overlap
+        for (int tok0 = rg; tok0 < g.bt; tok0 += 8 * rows_par) {
+            uint4 u[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int tok = tok0 + i * rows_par;
+                const int r = tok / g.tw, c = tok - r * g.tw;
+                u[i] = make_uint4(0, 0, 0, 0);
+                if (tok < g.bt && r < t.vh && c < t.vw) {
+                    const int64_t token = ((int64_t)t.frame * g.H + t.by * g.th + r) * g.W + t.bx * g.tw + c;
+                    u[i] = *(const uint4 *)(x + (token * st + (int64_t)head * sh + j * VEC) * ELT);
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
                 float f[VEC];
-                Unpack<VEC>::to_float(u, f);
+                Unpack<VEC>::to_float(u[i], f);       // zeros for padding add nothing
 #pragma unroll
                 for (int e = 0; e < VEC; ++e) acc[e] += f[e];
             }

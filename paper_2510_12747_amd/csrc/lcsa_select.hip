@@ -53,12 +53,21 @@ __global__ __launch_bounds__(64) void select_kernel(KGeom g, KCache c, const flo
         const int slot = slot_of_frame(c.start, g.cap, f);
         const float4 *kr = (const float4 *)(c.pooled + (((int64_t)head * g.cap + slot) * g.nb + t) * g.d);
         float s = 0.f;
-        for (int e = 0; e < g.d / 4; ++e) {
-            const float4 kk = kr[e];
-            s = fmaf(qs[4 * e], kk.x, s);
-            s = fmaf(qs[4 * e + 1], kk.y, s);
-            s = fmaf(qs[4 * e + 2], kk.z, s);
-            s = fmaf(qs[4 * e + 3], kk.w, s);
+        // the pooled-K row is fetched 16 float4 at a time so that the loads overlap instead of each
+        // FMA group waiting out one L2 round trip
+        const int n4 = g.d / 4;
+        for (int e0 = 0; e0 < n4; e0 += 16) {
+            float4 kk[16];
+#pragma unroll
+            for (int u = 0; u < 16; ++u) kk[u] = e0 + u < n4 ? kr[e0 + u] : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+            for (int u = 0; u < 16; ++u) {
+                const int e = (e0 + u < n4 ? e0 + u : 0) * 4;
+                s = fmaf(qs[e], kk[u].x, s);
+                s = fmaf(qs[e + 1], kk[u].y, s);
+                s = fmaf(qs[e + 2], kk[u].z, s);
+                s = fmaf(qs[e + 3], kk[u].w, s);
+            }
         }
         keys[ci] = order_key(s);
     }
