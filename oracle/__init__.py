@@ -56,7 +56,7 @@ _ci, _cl = ctypes.c_int, ctypes.c_int64
 
 @dataclass(frozen=True)
 class Geometry:
-    """Problem geometry in the paper's terms (one block = one th x tw tile of one frame)."""
+    """Problem geometry in the paper's terms (one block = tile_t frames x one th x tw tile)."""
     heads: int
     head_dim: int
     grid_h: int
@@ -68,6 +68,7 @@ class Geometry:
     radius_w: int
     topk: int
     window_mode: int = 0   # 0 boundary-truncated, 1 boundary-preserved
+    tile_t: int = 1        # frames per block; the paper's blocks are (tile_t, tile_h, tile_w) = (2, 8, 8)
 
     @property
     def nb(self) -> int:
@@ -89,12 +90,12 @@ def _tokens_view(x: np.ndarray):
 
 
 def pool(x: np.ndarray, g: Geometry, n_frames: int) -> np.ndarray:
-    """Block means of x -> float64 [heads][n_frames*nb][d]  (Sec. 3.2)."""
+    """Block means of x -> float64 [heads][(n_frames/tile_t)*nb][d]  (Sec. 3.2)."""
     x, st, sh = _tokens_view(x)
-    assert x.shape == (n_frames * g.tokens_per_frame, g.heads, g.head_dim)
-    out = np.empty((g.heads, n_frames * g.nb, g.head_dim), np.float64)
+    assert x.shape == (n_frames * g.tokens_per_frame, g.heads, g.head_dim) and n_frames % g.tile_t == 0
+    out = np.empty((g.heads, n_frames // g.tile_t * g.nb, g.head_dim), np.float64)
     _load().lcsa_oracle_pool(_p(x, _f32), _cl(st), _cl(sh), _ci(g.heads), _ci(g.head_dim),
-                             _ci(n_frames), _ci(g.grid_h), _ci(g.grid_w), _ci(g.tile_h), _ci(g.tile_w),
+                             _ci(n_frames), _ci(g.grid_h), _ci(g.grid_w), _ci(g.tile_t), _ci(g.tile_h), _ci(g.tile_w),
                              _p(out, _f64))
     return out
 
@@ -120,12 +121,13 @@ def allowed(qb: int, kb: int, g: Geometry) -> bool:
 def select(S: np.ndarray, g: Geometry, kv_frames: int):
     """Top-k admissible key blocks per (head, query block): (sel_idx, sel_cnt, gap)."""
     S = np.ascontiguousarray(S, np.float64)
-    n_qb, n_kb = g.q_frames * g.nb, kv_frames * g.nb
+    assert g.q_frames % g.tile_t == 0 and kv_frames % g.tile_t == 0
+    n_qb, n_kb = g.q_frames // g.tile_t * g.nb, kv_frames // g.tile_t * g.nb
     assert S.shape == (g.heads, n_qb, n_kb)
     sel_idx = np.empty((g.heads, n_qb, g.topk), np.int32)
     sel_cnt = np.empty((g.heads, n_qb), np.int32)
     gap = np.empty((g.heads, n_qb), np.float64)
-    _load().lcsa_oracle_select(_p(S, _f64), _ci(g.heads), _ci(g.q_frames), _ci(kv_frames),
+    _load().lcsa_oracle_select(_p(S, _f64), _ci(g.heads), _ci(g.q_frames // g.tile_t), _ci(kv_frames // g.tile_t),
                                _ci(g.grid_h), _ci(g.grid_w), _ci(g.tile_h), _ci(g.tile_w),
                                _ci(g.radius_h), _ci(g.radius_w), _ci(g.window_mode), _ci(g.topk),
                                _p(sel_idx, _i32), _p(sel_cnt, _i32), _p(gap, _f64))
@@ -152,7 +154,7 @@ def attend(q: np.ndarray, k: np.ndarray, v: np.ndarray, g: Geometry, kv_frames: 
     sel_idx = np.ascontiguousarray(sel_idx, np.int32)
     sel_cnt = np.ascontiguousarray(sel_cnt, np.int32)
     topk = sel_idx.shape[-1]
-    assert sel_idx.shape == (g.heads, g.q_frames * g.nb, topk)
+    assert sel_idx.shape == (g.heads, g.q_frames // g.tile_t * g.nb, topk)
     o = np.full((q.shape[0], g.heads, g.head_dim), np.nan, np.float64)
     lse = np.full((q.shape[0], g.heads), np.nan, np.float64) if with_lse else None
     if rows is None:
@@ -162,7 +164,7 @@ def attend(q: np.ndarray, k: np.ndarray, v: np.ndarray, g: Geometry, kv_frames: 
         rows_p, n_rows = _p(rows, _i32), rows.shape[0]
     _load().lcsa_oracle_attend(_p(q, _f32), _cl(qst), _cl(qsh), _p(k, _f32), _p(v, _f32), _cl(kst), _cl(ksh),
                                _ci(g.heads), _ci(g.head_dim), _ci(g.q_frames), _ci(kv_frames),
-                               _ci(g.grid_h), _ci(g.grid_w), _ci(g.tile_h), _ci(g.tile_w),
+                               _ci(g.grid_h), _ci(g.grid_w), _ci(g.tile_t), _ci(g.tile_h), _ci(g.tile_w),
                                _p(sel_idx, _i32), _p(sel_cnt, _i32), _ci(topk), _f64(scale),
                                rows_p, _ci(n_rows), _p(o, _f64), _p(lse, _f64) if with_lse else None)
     return (o, lse) if with_lse else o
@@ -178,7 +180,7 @@ def attend_weights(q, k, v, g: Geometry, kv_frames: int, blocks, head: int, q_to
     o = np.empty(g.head_dim, np.float64)
     _load().lcsa_oracle_attend_weights(_p(q, _f32), _cl(qst), _cl(qsh), _p(k, _f32), _p(v, _f32), _cl(kst), _cl(ksh),
                                        _ci(g.head_dim), _ci(kv_frames), _ci(g.grid_h), _ci(g.grid_w),
-                                       _ci(g.tile_h), _ci(g.tile_w), _p(blocks, _i32), _ci(len(blocks)),
+                                       _ci(g.tile_t), _ci(g.tile_h), _ci(g.tile_w), _p(blocks, _i32), _ci(len(blocks)),
                                        _f64(scale), _ci(head), _cl(q_tok), _p(o, _f64), _p(w, _f64))
     return w, o
 

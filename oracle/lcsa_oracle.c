@@ -19,10 +19,12 @@
  *     (a bf16 value widened to float is exact); every sum, product, mean,
  *     exponential and division below is carried out in double.
  *   - x[token][head][c] is addressed as x[token*stride_tok + head*stride_head + c].
- *   - A block is one th x tw spatial tile of one frame.  Tiles on the right /
- *     bottom edge of a grid that th / tw do not divide hold fewer tokens.
- *   - Block id = frame * nb + by * tx + bx with nb = ty * tx, frame 0 = oldest
- *     visible frame for keys, first frame of the chunk for queries.
+ *   - A block is tt consecutive frames x one th x tw spatial tile (Sec. 3.2 uses
+ *     (tt,th,tw) = (2,8,8); tt = 1 gives single-frame tiles).  Tiles on the right /
+ *     bottom edge of a grid that th / tw do not divide hold fewer tokens.  Frame
+ *     counts are multiples of tt.
+ *   - Block id = group * nb + by * tx + bx with nb = ty * tx and group = frame / tt,
+ *     group 0 = oldest visible frames for keys, first frames of the chunk for queries.
  *
  * Pins (tests/test_oracle_pins.py): brute-force dense softmax attention,
  * windowed dense attention, hand-written window sets, the Q = 0 closed form,
@@ -56,27 +58,28 @@ int lcsa_oracle_blocks_per_frame(int H, int W, int th, int tw)
 
 /* ---- Sec. 3.2: average pooling inside each block --------------------------------- */
 
-/* pooled[head][frame*nb + tile][c] = mean over the tile's tokens of x. */
+/* pooled[head][group*nb + tile][c] = mean over the block's tokens of x (n_frames = multiple of tt). */
 void lcsa_oracle_pool(const float *x, int64_t stride_tok, int64_t stride_head,
-                      int heads, int d, int n_frames, int H, int W, int th, int tw,
+                      int heads, int d, int n_frames, int H, int W, int tt, int th, int tw,
                       double *pooled)
 {
-    const int ty = ceil_div(H, th), tx = ceil_div(W, tw), nb = ty * tx;
+    const int ty = ceil_div(H, th), tx = ceil_div(W, tw), nb = ty * tx, n_groups = n_frames / tt;
     for (int h = 0; h < heads; ++h)
-        for (int f = 0; f < n_frames; ++f)
+        for (int g = 0; g < n_groups; ++g)
             for (int by = 0; by < ty; ++by)
                 for (int bx = 0; bx < tx; ++bx) {
                     int r0, r1, c0, c1;
                     tile_extent(by, bx, H, W, th, tw, &r0, &r1, &c0, &c1);
-                    double *out = pooled + ((int64_t)h * n_frames * nb + (int64_t)f * nb + by * tx + bx) * d;
+                    double *out = pooled + ((int64_t)h * n_groups * nb + (int64_t)g * nb + by * tx + bx) * d;
                     for (int c = 0; c < d; ++c) {
                         double sum = 0.0;
-                        for (int r = r0; r < r1; ++r)
-                            for (int col = c0; col < c1; ++col) {
-                                int64_t tok = ((int64_t)f * H + r) * W + col;
-                                sum += (double)x[tok * stride_tok + h * stride_head + c];
-                            }
-                        out[c] = sum / (double)((r1 - r0) * (c1 - c0));
+                        for (int f = g * tt; f < (g + 1) * tt; ++f)
+                            for (int r = r0; r < r1; ++r)
+                                for (int col = c0; col < c1; ++col) {
+                                    int64_t tok = ((int64_t)f * H + r) * W + col;
+                                    sum += (double)x[tok * stride_tok + h * stride_head + c];
+                                }
+                        out[c] = sum / (double)(tt * (r1 - r0) * (c1 - c0));
                     }
                 }
 }
@@ -164,13 +167,13 @@ static int int_ascending(const void *pa, const void *pb)
  * gap = score of the last kept block minus the best score left out
  * (+inf when nothing admissible is left out).
  */
-void lcsa_oracle_select(const double *S, int heads, int q_frames, int kv_frames,
+void lcsa_oracle_select(const double *S, int heads, int q_groups, int kv_groups,
                         int H, int W, int th, int tw,
                         int radius_h, int radius_w, int window_mode, int topk,
                         int32_t *sel_idx, int32_t *sel_cnt, double *gap)
 {
     const int nb = lcsa_oracle_blocks_per_frame(H, W, th, tw);
-    const int n_qb = q_frames * nb, n_kb = kv_frames * nb;
+    const int n_qb = q_groups * nb, n_kb = kv_groups * nb;   /* groups = frames / tt */
     cand_t *cand = (cand_t *)malloc(sizeof(cand_t) * (size_t)n_kb);
     for (int h = 0; h < heads; ++h)
         for (int qb = 0; qb < n_qb; ++qb) {
@@ -202,27 +205,28 @@ void lcsa_oracle_select(const double *S, int heads, int q_frames, int kv_frames,
  * (length kv_frames*H*W, zero for tokens outside the listed blocks).
  */
 static void attend_token(const float *q_tok, const float *k, const float *v,
-                         int64_t kv_stride_tok, int d, int H, int W, int th, int tw,
+                         int64_t kv_stride_tok, int d, int H, int W, int tt, int th, int tw,
                          const int32_t *blocks, int n_blocks, double scale,
-                         double *logit /* scratch, >= n_blocks*th*tw */,
+                         double *logit /* scratch, >= n_blocks*tt*th*tw */,
                          int64_t *tok_of /* scratch, same length */,
                          double *o, double *lse, double *weights)
 {
     const int ty = ceil_div(H, th), tx = ceil_div(W, tw), nb = ty * tx;
     int n = 0;
     for (int b = 0; b < n_blocks; ++b) {
-        int kb = blocks[b], f = kb / nb, t = kb % nb, r0, r1, c0, c1;
+        int kb = blocks[b], g = kb / nb, t = kb % nb, r0, r1, c0, c1;
         tile_extent(t / tx, t % tx, H, W, th, tw, &r0, &r1, &c0, &c1);
-        for (int r = r0; r < r1; ++r)
-            for (int c = c0; c < c1; ++c) {
-                int64_t tok = ((int64_t)f * H + r) * W + c;
-                const float *kj = k + tok * kv_stride_tok;
-                double dot = 0.0;
-                for (int e = 0; e < d; ++e) dot += (double)q_tok[e] * (double)kj[e];
-                logit[n] = dot * scale;
-                tok_of[n] = tok;
-                ++n;
-            }
+        for (int f = g * tt; f < (g + 1) * tt; ++f)
+            for (int r = r0; r < r1; ++r)
+                for (int c = c0; c < c1; ++c) {
+                    int64_t tok = ((int64_t)f * H + r) * W + c;
+                    const float *kj = k + tok * kv_stride_tok;
+                    double dot = 0.0;
+                    for (int e = 0; e < d; ++e) dot += (double)q_tok[e] * (double)kj[e];
+                    logit[n] = dot * scale;
+                    tok_of[n] = tok;
+                    ++n;
+                }
     }
     for (int e = 0; e < d; ++e) o[e] = 0.0;
     if (n == 0) { if (lse) *lse = -INFINITY; return; }
@@ -250,36 +254,38 @@ static void attend_token(const float *q_tok, const float *k, const float *v,
 void lcsa_oracle_attend(const float *q, int64_t q_stride_tok, int64_t q_stride_head,
                         const float *k, const float *v, int64_t kv_stride_tok, int64_t kv_stride_head,
                         int heads, int d, int q_frames, int kv_frames,
-                        int H, int W, int th, int tw,
+                        int H, int W, int tt, int th, int tw,
                         const int32_t *sel_idx, const int32_t *sel_cnt, int topk,
                         double scale, const int32_t *rows, int n_rows,
                         double *o, double *lse)
 {
     const int ty = ceil_div(H, th), tx = ceil_div(W, tw), nb = ty * tx;
-    const int n_qb = q_frames * nb;
+    const int n_qb = (q_frames / tt) * nb;
+    (void)kv_frames;
     const int total = n_rows < 0 ? heads * n_qb : n_rows;
     if (scale <= 0.0) scale = 1.0 / sqrt((double)d);
 #pragma omp parallel
     {
-        double *logit = (double *)malloc(sizeof(double) * (size_t)topk * th * tw);
-        int64_t *tok_of = (int64_t *)malloc(sizeof(int64_t) * (size_t)topk * th * tw);
+        double *logit = (double *)malloc(sizeof(double) * (size_t)topk * tt * th * tw);
+        int64_t *tok_of = (int64_t *)malloc(sizeof(int64_t) * (size_t)topk * tt * th * tw);
 #pragma omp for schedule(dynamic, 1)
         for (int it = 0; it < total; ++it) {
             int h = n_rows < 0 ? it / n_qb : rows[2 * it];
             int qb = n_rows < 0 ? it % n_qb : rows[2 * it + 1];
-            int f = qb / nb, t = qb % nb, r0, r1, c0, c1;
+            int g = qb / nb, t = qb % nb, r0, r1, c0, c1;
             tile_extent(t / tx, t % tx, H, W, th, tw, &r0, &r1, &c0, &c1);
             const int32_t *blocks = sel_idx + ((int64_t)h * n_qb + qb) * topk;
             int n_blocks = sel_cnt[(int64_t)h * n_qb + qb];
-            for (int r = r0; r < r1; ++r)
-                for (int c = c0; c < c1; ++c) {
-                    int64_t tok = ((int64_t)f * H + r) * W + c;
-                    attend_token(q + tok * q_stride_tok + h * q_stride_head,
-                                 k + h * kv_stride_head, v + h * kv_stride_head,
-                                 kv_stride_tok, d, H, W, th, tw, blocks, n_blocks, scale,
-                                 logit, tok_of, o + (tok * heads + h) * d,
-                                 lse ? lse + tok * heads + h : NULL, NULL);
-                }
+            for (int f = g * tt; f < (g + 1) * tt; ++f)
+                for (int r = r0; r < r1; ++r)
+                    for (int c = c0; c < c1; ++c) {
+                        int64_t tok = ((int64_t)f * H + r) * W + c;
+                        attend_token(q + tok * q_stride_tok + h * q_stride_head,
+                                     k + h * kv_stride_head, v + h * kv_stride_head,
+                                     kv_stride_tok, d, H, W, tt, th, tw, blocks, n_blocks, scale,
+                                     logit, tok_of, o + (tok * heads + h) * d,
+                                     lse ? lse + tok * heads + h : NULL, NULL);
+                    }
         }
         free(logit);
         free(tok_of);
@@ -294,18 +300,18 @@ void lcsa_oracle_attend(const float *q, int64_t q_stride_tok, int64_t q_stride_h
  */
 void lcsa_oracle_attend_weights(const float *q, int64_t q_stride_tok, int64_t q_stride_head,
                                 const float *k, const float *v, int64_t kv_stride_tok, int64_t kv_stride_head,
-                                int d, int kv_frames, int H, int W, int th, int tw,
+                                int d, int kv_frames, int H, int W, int tt, int th, int tw,
                                 const int32_t *blocks, int n_blocks, double scale,
                                 int h, int64_t q_tok, double *o, double *weights)
 {
     (void)kv_frames;
     if (scale <= 0.0) scale = 1.0 / sqrt((double)d);
-    int cap = (n_blocks > 0 ? n_blocks : 1) * th * tw;
+    int cap = (n_blocks > 0 ? n_blocks : 1) * tt * th * tw;
     double *logit = (double *)malloc(sizeof(double) * (size_t)cap);
     int64_t *tok_of = (int64_t *)malloc(sizeof(int64_t) * (size_t)cap);
     attend_token(q + q_tok * q_stride_tok + h * q_stride_head,
                  k + h * kv_stride_head, v + h * kv_stride_head, kv_stride_tok,
-                 d, H, W, th, tw, blocks, n_blocks, scale, logit, tok_of, o, NULL, weights);
+                 d, H, W, tt, th, tw, blocks, n_blocks, scale, logit, tok_of, o, NULL, weights);
     free(logit);
     free(tok_of);
 }

@@ -272,3 +272,11 @@ def test_late_dominant_block_redoes_softmax_reference():
     check_outputs(o, q, K, V, og2, 6, s_idx, s_cnt, None)
     _, want_lse = oracle.attend(q, K, V, og2, 6, s_idx, s_cnt, with_lse=True)
     np.testing.assert_allclose(lse.cpu().numpy(), want_lse, rtol=0, atol=5e-3)
+
+
+def test_more_than_64_selected_blocks_refills_the_id_chunk():
+    """90 key blocks per row (15 tiles x 6 frames, unbounded window, k >= all): the attention kernel
+    keeps 64 block ids at a time in registers and has to refill them once per row."""
+    w = wl.with_overrides(wl.WORKLOADS["small"], name="refill", heads=1, grid_h=40, grid_w=48, radius=-1, topk=128)
+    p, r = run_primed(w, check_lse=True)
+    assert r.rows_checked == 30

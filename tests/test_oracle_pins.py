@@ -357,3 +357,41 @@ def test_rows_argument_restricts_work():
     want = sorted([r * 8 + c for r in (4, 5) for c in range(4, 8)] + [48 + r * 8 + c for r in (4, 5) for c in range(4)])
     assert list(np.nonzero(done)[0]) == want
     np.testing.assert_array_equal(part[done], full["o"][done])
+
+
+# ---- blocks with a temporal extent: the paper's (2, 8, 8) partition (Sec. 3.2) ---------------------
+def test_temporal_blocks_reduce_to_dense_attention():
+    g = Geometry(2, 8, 5, 6, 2, 4, q_frames=2, radius_h=-1, radius_w=-1, topk=100, tile_t=2)   # ragged in both axes
+    kv = 4
+    rng = np.random.default_rng(31)
+    q, k, v = rand_qkv(rng, g, kv)
+    res = oracle.lcsa(q, k, v, g, kv)
+    assert res["sel_idx"].shape == (2, 1 * g.nb, 100) and (res["sel_cnt"] == 2 * g.nb).all()
+    want, want_lse = dense_attention(q, k, v)
+    np.testing.assert_allclose(res["o"], want, rtol=0, atol=1e-12)
+
+
+def test_temporal_blocks_pool_over_both_frames():
+    g = Geometry(1, 3, 4, 6, 2, 3, q_frames=4, radius_h=-1, radius_w=-1, topk=1, tile_t=2)
+    x = np.random.default_rng(32).standard_normal((4 * 24, 1, 3)).astype(np.float32)
+    want = x.astype(np.float64).reshape(2, 2, 2, 2, 2, 3, 1, 3).mean(axis=(1, 3, 5))   # group, ft, by, r, bx, c, h, d
+    want = want.transpose(3, 0, 1, 2, 4).reshape(1, 2 * 4, 3)
+    np.testing.assert_allclose(oracle.pool(x, g, 4), want, rtol=0, atol=1e-15)
+
+
+def test_temporal_blocks_zero_queries_and_window():
+    """Q = 0 with (2, 4, 4) blocks on a 6 x 8 grid: kept blocks are the lowest ids of the OLDEST frame pair;
+    the window is spatial only, so both frames of a block are always taken together."""
+    g = Geometry(1, 8, 6, 8, 4, 4, q_frames=2, radius_h=0, radius_w=4, topk=2, tile_t=2)   # same tile row, +-1 tile column
+    kv = 4
+    rng = np.random.default_rng(33)
+    q, k, v = rand_qkv(rng, g, kv)
+    q[:] = 0
+    res = oracle.lcsa(q, k, v, g, kv)
+    assert g.nb == 4 and res["sel_idx"].shape == (1, 4, 2)
+    np.testing.assert_array_equal(res["sel_idx"][0], [[0, 1], [0, 1], [2, 3], [2, 3]])
+    # query tile 2 (bottom-left, rows 4,5): kept tiles 2 and 3 of frames 0 and 1 -> rows 4,5 x all 8 columns x 2 frames
+    toks = [f * 48 + r * 8 + c for f in (0, 1) for r in (4, 5) for c in range(8)]
+    want = v[toks].astype(np.float64).mean(axis=0)[0]
+    q_toks = [f * 48 + r * 8 + c for f in (0, 1) for r in (4, 5) for c in range(4)]
+    np.testing.assert_allclose(res["o"][q_toks, 0], np.broadcast_to(want, (16, 8)), rtol=0, atol=1e-14)
