@@ -48,6 +48,7 @@ def main() -> int:
     ap.add_argument("--layers", type=int, default=0, help="override the workload's number of layer calls")
     ap.add_argument("--topk", type=int, default=0, help="override top-k (a value >= the window size gives windowed dense attention)")
     ap.add_argument("--radius", type=int, default=None, help="override the locality radius in tokens (-1: unbounded window)")
+    ap.add_argument("--blocks", default="", help="block shape t,h,w overriding the workload's 1,tile_h,tile_w (e.g. 2,8,8: the paper's partition)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device-to-device copy (reference point for HBM byte counters)")
@@ -69,9 +70,13 @@ def main() -> int:
     n_layers = args.layers or w.n_layers
     topk = args.topk or w.topk
     radius = w.radius if args.radius is None else args.radius
+    tile_t = 1
+    if args.blocks:
+        tile_t, th, tw = (int(x) for x in args.blocks.split(","))
+        w = wl.with_overrides(w, tile_h=th, tile_w=tw)
     g = B.Geom(w.heads, w.head_dim, w.grid_h, w.grid_w, w.tile_h, w.tile_w, w.q_frames, w.cache_frames,
-               radius, radius, topk, dtype=B.LCSA_BF16)
-    n_qb = g.q_frames * g.nb
+               radius, radius, topk, dtype=B.LCSA_BF16, tile_t=tile_t)
+    n_qb = g.n_qb
 
     def dev(x):
         return torch.from_numpy(wl.bf16_bits(x).view(np.int16)).view(torch.bfloat16).cuda()
@@ -158,7 +163,7 @@ def main() -> int:
     ty, tx = -(-w.grid_h // w.tile_h), -(-w.grid_w // w.tile_w)
     vh = np.minimum(w.tile_h, w.grid_h - np.arange(ty) * w.tile_h)
     vw = np.minimum(w.tile_w, w.grid_w - np.arange(tx) * w.tile_w)
-    valid_tok = (vh[:, None] * vw[None, :]).reshape(-1)              # valid tokens per tile
+    valid_tok = (vh[:, None] * vw[None, :]).reshape(-1) * tile_t     # valid tokens per block
     useful, issued = [], []
     for L in layers:
         idx = L["sel_idx"].cpu().numpy()
@@ -173,8 +178,8 @@ def main() -> int:
 
     # append traffic (algorithmic): read new K,V once, write their tiles once, write pooled K
     tok_new = w.q_frames * w.tokens_per_frame
-    append_bytes = 2 * tok_new * g.heads * g.head_dim * 2 + 2 * w.q_frames * g.nb * 128 * 128 * 2 * g.heads \
-        + w.q_frames * g.nb * g.heads * g.head_dim * 4
+    append_bytes = 2 * tok_new * g.heads * g.head_dim * 2 + 2 * n_qb * 128 * 128 * 2 * g.heads \
+        + n_qb * g.heads * g.head_dim * 4
     pool_bytes = tok_new * g.heads * g.head_dim * 2 + n_qb * g.heads * g.head_dim * 4
 
     out = {
@@ -192,7 +197,8 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": WORKLOAD_TEXT[args.workload], "heads": g.heads, "head_dim": g.head_dim,
                    "layers_per_step": n_layers, "q_tokens": tok_new, "kv_tokens": w.cache_frames * w.tokens_per_frame,
-                   "blocks_per_frame": g.nb, "topk": topk, "radius": radius},
+                   "block_shape": [tile_t, w.tile_h, w.tile_w], "blocks_per_group": g.nb, "query_blocks": n_qb,
+                   "topk": topk, "radius": radius},
         "effective_tflops_whole_path": round(useful_flop / (ms_per_layer * 1e-3) / 1e12, 2),
         "kernel_ms_per_layer": {"kv_cache_append": round(float(brk[0]), 5), "pool_blocks": round(float(brk[1]), 5),
                                 "select_blocks": round(float(brk[2]), 5), "sparse_attn_fwd": round(attn_avg_ms, 5)},
@@ -213,7 +219,7 @@ def main() -> int:
     if not args.no_cpu_baseline:
         import oracle
         og = oracle.Geometry(w.heads, w.head_dim, w.grid_h, w.grid_w, w.tile_h, w.tile_w, w.q_frames,
-                             radius, radius, topk)
+                             radius, radius, topk, tile_t=tile_t)
         times = []
         for layer in range(min(5, n_layers)):
             chunks = host_layer0 if layer == 0 else gen(layer)

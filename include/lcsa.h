@@ -21,12 +21,14 @@
  *     Element (token, head, c) of x is x[token*stride_tok + head*stride_head + c];
  *     strides are in elements, c is contiguous.  Base pointers must be 16-byte
  *     aligned and strides multiples of 16 bytes.
- *   - A block is one tile_h x tile_w tile of one frame; tiles on the right and
- *     bottom edge of a grid the tile does not divide hold fewer (valid) tokens.
- *     nb = ceil(grid_h/tile_h)*ceil(grid_w/tile_w) blocks per frame.  Block id =
- *     frame*nb + tile_row*ceil(grid_w/tile_w) + tile_col.  For key blocks frame 0
- *     is the OLDEST frame currently visible in the cache and the chunk's own
- *     frames come last; for query blocks frame 0 is the chunk's first frame.
+ *   - A block is tile_t consecutive frames x one tile_h x tile_w tile (Sec. 3.2 uses
+ *     (2,8,8); tile_t = 1 gives single-frame tiles); tiles on the right and bottom
+ *     edge of a grid the tile does not divide hold fewer (valid) tokens.  Frame counts
+ *     (q_frames, cache_frames, every append) are multiples of tile_t; a "group" is
+ *     tile_t consecutive frames.  nb = ceil(grid_h/tile_h)*ceil(grid_w/tile_w) blocks
+ *     per group.  Block id = group*nb + tile_row*ceil(grid_w/tile_w) + tile_col.  For
+ *     key blocks group 0 holds the OLDEST frames currently visible in the cache and the
+ *     chunk's own frames come last; for query blocks group 0 starts the chunk.
  *   - Return value: LCSA_OK or a negative lcsa_status.  Nothing is enqueued
  *     when a call fails validation.  No call aborts, throws or prints.
  */
@@ -56,8 +58,9 @@ typedef struct lcsa_geom {
     int32_t head_dim;      /* d; multiple of 8 (bf16) / 4 (f32), at most 256                         */
     int32_t grid_h;        /* latent tokens per frame: rows                                          */
     int32_t grid_w;        /*                          columns                                       */
-    int32_t tile_h;        /* block = tile_h x tile_w tokens of one frame (Sec. 3.2)                 */
+    int32_t tile_h;        /* block = tile_t frames x tile_h x tile_w tokens (Sec. 3.2)              */
     int32_t tile_w;
+    int32_t tile_t;        /* frames per block; divides q_frames and cache_frames                    */
     int32_t q_frames;      /* frames per chunk (queries)                                             */
     int32_t cache_frames;  /* sliding-window capacity in frames, the current chunk included          */
     int32_t radius_h;      /* local window: max distance of block centres in tokens, per axis;       */
@@ -89,8 +92,8 @@ void lcsa_cache_free(lcsa_cache *cache);
 int32_t lcsa_cache_valid_frames(const lcsa_cache *cache);
 /*
  * Inspection helpers for tests.  Pooled keys live in the cache as float
- * [heads][cache_frames*nb][head_dim], indexed by ring slot: the block `tile` of visible
- * frame f (0 = oldest) is row lcsa_cache_frame_slot(cache, f)*nb + tile.
+ * [heads][(cache_frames/tile_t)*nb][head_dim], indexed by ring slot: the block `tile` of the
+ * group that holds visible frame f (0 = oldest) is row lcsa_cache_frame_slot(cache, f)*nb + tile.
  */
 const float *lcsa_cache_pooled_k_device(const lcsa_cache *cache);
 int32_t lcsa_cache_frame_slot(const lcsa_cache *cache, int32_t frame);
@@ -99,7 +102,7 @@ int32_t lcsa_cache_frame_slot(const lcsa_cache *cache, int32_t frame);
  * Appends the keys and values of n_frames new frames (device, raster order, the cache's
  * dtype, shared strides) and evicts the oldest frames beyond the capacity: sliding-window
  * eviction, the paper's default.  Also stores the block means of the new keys (Sec. 3.2
- * average pooling) for lcsa_select_blocks.  1 <= n_frames <= cache_frames.
+ * average pooling) for lcsa_select_blocks.  1 <= n_frames <= cache_frames, a multiple of tile_t.
  */
 int32_t lcsa_kv_cache_append(lcsa_cache *cache, const void *k, const void *v,
                              int64_t stride_tok, int64_t stride_head,
@@ -108,8 +111,9 @@ int32_t lcsa_kv_cache_append(lcsa_cache *cache, const void *k, const void *v,
 /* ---- block pooling (Sec. 3.2: average pooling inside each block) ------------------------------ */
 
 /*
- * pooled[head][frame*nb + tile][c] = mean of x over the VALID tokens of the block
- * (device float [heads][n_frames*nb][head_dim], written in full).  x: device, geom->dtype.
+ * pooled[head][group*nb + tile][c] = mean of x over the VALID tokens of the block
+ * (device float [heads][(n_frames/tile_t)*nb][head_dim], written in full).  x: device,
+ * geom->dtype; n_frames a multiple of tile_t.
  */
 int32_t lcsa_pool_blocks(const lcsa_geom *geom, const void *x,
                          int64_t stride_tok, int64_t stride_head,
@@ -122,11 +126,11 @@ int32_t lcsa_pool_blocks(const lcsa_geom *geom, const void *x,
  * accumulation) for every key block kb of every visible frame whose tile lies inside
  * qb's spatial window; keeps the m = min(topk, #admissible) best, equal scores going to
  * the lower key-block id.
- *   sel_idx  device int32 [heads][q_frames*nb][topk]: kept ids ascending, then -1
- *   sel_cnt  device int32 [heads][q_frames*nb]: m
- *   gap      device float [heads][q_frames*nb] or NULL: score of the weakest kept block
+ *   sel_idx  device int32 [heads][n_qb][topk], n_qb = (q_frames/tile_t)*nb: kept ids ascending, then -1
+ *   sel_cnt  device int32 [heads][n_qb]: m
+ *   gap      device float [heads][n_qb] or NULL: score of the weakest kept block
  *            minus the best admissible score left out (+inf if none is left out)
- * pooled_q: device float [heads][q_frames*nb][head_dim] from lcsa_pool_blocks.
+ * pooled_q: device float [heads][n_qb][head_dim] from lcsa_pool_blocks.
  * The cache must hold at least q_frames frames.  At most 8192 admissible key blocks
  * per row (LCSA_EUNSUPPORTED beyond).
  */

@@ -27,7 +27,7 @@ class LcsaError(RuntimeError):
 
 class lcsa_geom(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in (
-        "heads", "head_dim", "grid_h", "grid_w", "tile_h", "tile_w", "q_frames", "cache_frames",
+        "heads", "head_dim", "grid_h", "grid_w", "tile_h", "tile_w", "tile_t", "q_frames", "cache_frames",
         "radius_h", "radius_w", "window_mode", "topk", "dtype")]
 
 
@@ -46,9 +46,10 @@ class Geom:
     topk: int
     dtype: int = LCSA_BF16
     window_mode: int = WINDOW_TRUNCATED
+    tile_t: int = 1          # frames per block; (tile_t, tile_h, tile_w) = (2, 8, 8) is the paper's partition
 
     def c(self) -> lcsa_geom:
-        return lcsa_geom(self.heads, self.head_dim, self.grid_h, self.grid_w, self.tile_h, self.tile_w,
+        return lcsa_geom(self.heads, self.head_dim, self.grid_h, self.grid_w, self.tile_h, self.tile_w, self.tile_t,
                          self.q_frames, self.cache_frames, self.radius_h, self.radius_w, self.window_mode,
                          self.topk, self.dtype)
 
@@ -59,6 +60,11 @@ class Geom:
     @property
     def tokens_per_frame(self) -> int:
         return self.grid_h * self.grid_w
+
+    @property
+    def n_qb(self) -> int:
+        """Query blocks per chunk."""
+        return self.q_frames // self.tile_t * self.nb
 
     @property
     def torch_dtype(self):
@@ -172,12 +178,13 @@ def lcsa_cache_frame_slot(cache: Cache, frame: int) -> int:
 
 
 def lcsa_cache_pooled_k(cache: Cache) -> torch.Tensor:
-    """Pooled keys as a float tensor view [heads][cache_frames*nb][d] over the cache storage (ring-slot order)."""
+    """Pooled keys as a float tensor view [heads][(cache_frames/tile_t)*nb][d] over the cache storage (ring-slot order)."""
     g = cache.geom
     ptr = lib().lcsa_cache_pooled_k_device(cache.handle)
     off = ptr - cache.storage.data_ptr()
-    n = g.heads * g.cache_frames * g.nb * g.head_dim
-    return cache.storage[off:off + 4 * n].view(torch.float32).view(g.heads, g.cache_frames * g.nb, g.head_dim)
+    rows = g.cache_frames // g.tile_t * g.nb
+    n = g.heads * rows * g.head_dim
+    return cache.storage[off:off + 4 * n].view(torch.float32).view(g.heads, rows, g.head_dim)
 
 
 def lcsa_kv_cache_append(cache: Cache, k: torch.Tensor, v: torch.Tensor, n_frames: int, stream=None) -> None:
@@ -194,9 +201,10 @@ def lcsa_pool_blocks(geom: Geom, x: torch.Tensor, n_frames: int, pooled: torch.T
     xp, st, sh = _tok(x)
     if x.dtype != geom.torch_dtype or x.shape != (n_frames * geom.tokens_per_frame, geom.heads, geom.head_dim):
         raise LcsaError("lcsa_pool_blocks: shape/dtype mismatch")
+    n_blocks = n_frames // geom.tile_t * geom.nb
     if pooled is None:
-        pooled = torch.empty(geom.heads, n_frames * geom.nb, geom.head_dim, dtype=torch.float32, device=x.device)
-    assert pooled.is_contiguous() and pooled.dtype == torch.float32 and pooled.numel() == geom.heads * n_frames * geom.nb * geom.head_dim
+        pooled = torch.empty(geom.heads, n_blocks, geom.head_dim, dtype=torch.float32, device=x.device)
+    assert pooled.is_contiguous() and pooled.dtype == torch.float32 and pooled.numel() == geom.heads * n_blocks * geom.head_dim
     g = geom.c()
     _check(lib().lcsa_pool_blocks(ctypes.byref(g), xp, st, sh, n_frames, pooled.data_ptr(), _stream(stream)), "lcsa_pool_blocks")
     return pooled
@@ -204,7 +212,7 @@ def lcsa_pool_blocks(geom: Geom, x: torch.Tensor, n_frames: int, pooled: torch.T
 
 def lcsa_select_blocks(geom: Geom, pooled_q: torch.Tensor, cache: Cache, sel_idx=None, sel_cnt=None, gap=None,
                        want_gap: bool = True, stream=None):
-    n_qb = geom.q_frames * geom.nb
+    n_qb = geom.n_qb
     dev = pooled_q.device
     assert pooled_q.is_contiguous() and pooled_q.dtype == torch.float32 and pooled_q.shape == (geom.heads, n_qb, geom.head_dim)
     if sel_idx is None:
@@ -233,7 +241,7 @@ def lcsa_sparse_attn_fwd(geom: Geom, q: torch.Tensor, cache: Cache, sel_idx: tor
     op, ost, osh = _tok(o)
     assert o.shape == q.shape and o.dtype == q.dtype
     assert sel_idx.is_contiguous() and sel_cnt.is_contiguous() and sel_idx.dtype == torch.int32 and sel_cnt.dtype == torch.int32
-    assert sel_idx.numel() == geom.heads * geom.q_frames * geom.nb * geom.topk
+    assert sel_idx.numel() == geom.heads * geom.n_qb * geom.topk
     if lse is not None:
         assert lse.is_contiguous() and lse.dtype == torch.float32 and lse.shape == (q.shape[0], geom.heads)
     g = geom.c()

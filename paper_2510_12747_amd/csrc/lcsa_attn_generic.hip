@@ -60,7 +60,7 @@ __global__ __launch_bounds__(64 * kWaves) void attn_generic_kernel(
     constexpr int DPL = 4;                                  // channels per lane: e = lane + 64*jj
     const int qb = blockIdx.x, head = blockIdx.y;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int n_qb = g.q_frames * g.nb;
+    const int n_qb = g.q_groups * g.nb;
     const int fq = qb / g.nb, tile = qb - fq * g.nb, by = tile / g.tx, bx = tile - by * g.tx;
     const int qvh = min(g.th, g.H - by * g.th), qvw = min(g.tw, g.W - bx * g.tw);
     const int64_t row = (int64_t)head * n_qb + qb;
@@ -72,10 +72,10 @@ __global__ __launch_bounds__(64 * kWaves) void attn_generic_kernel(
     // wavefronts whose token is padding compute on a clamped token and store nothing
     for (int t0 = 0; t0 < g.bt; t0 += kWaves) {
         const int tq = t0 + wave;
-        const int r = tq / g.tw, cc = tq - r * g.tw;
-        const bool q_valid = tq < g.bt && r < qvh && cc < qvw;
-        const int64_t token = q_valid ? ((int64_t)fq * g.H + by * g.th + r) * g.W + bx * g.tw + cc
-                                      : ((int64_t)fq * g.H + by * g.th) * g.W + bx * g.tw;
+        int qft, r, cc;
+        const bool q_valid = block_token(g, tq, qvh, qvw, qft, r, cc);
+        const int64_t token = q_valid ? raster_token(g, fq, qft, by * g.th + r, bx * g.tw + cc)
+                                      : raster_token(g, fq, 0, by * g.th, bx * g.tw);
         __syncthreads();                                     // previous token's readers of qs are done
         for (int e = lane; e < g.d; e += 64) qs[wave][e] = Elt<T>::load(q + token * q_st + (int64_t)head * q_sh + e);
         __syncthreads();
@@ -88,8 +88,8 @@ __global__ __launch_bounds__(64 * kWaves) void attn_generic_kernel(
             const int64_t tbase = (((int64_t)head * g.cap + slot) * g.nb + kt) * g.bt * g.d;
             for (int base = 0; base < g.bt; base += 64) {
                 const int key = base + lane;
-                const int kr = key / g.tw, kcc = key - kr * g.tw;
-                const bool k_valid = key < g.bt && kr < vh && kcc < vw;
+                int kft, kr, kcc;
+                const bool k_valid = block_token(g, key, vh, vw, kft, kr, kcc);
                 float s = -__builtin_inff();
                 if (k_valid) {
                     const T *kp = kc + tbase + (int64_t)key * g.d;
@@ -144,7 +144,7 @@ __global__ __launch_bounds__(64 * kWaves) void attn_generic_kernel(
 hipError_t launch_attn_generic(const KGeom &g, const KCache &c, const void *q, int64_t q_st, int64_t q_sh,
                                const int32_t *sel_idx, const int32_t *sel_cnt,
                                void *o, int64_t o_st, int64_t o_sh, float *lse, float scale, hipStream_t stream) {
-    dim3 grid(g.q_frames * g.nb, g.heads);
+    dim3 grid(g.q_groups * g.nb, g.heads);
     const float scale_log2 = scale * kLog2e;
     if (g.bf16)
         attn_generic_kernel<__bf16><<<grid, 64 * kWaves, 0, stream>>>(g, c, (const __bf16 *)q, q_st, q_sh, sel_idx, sel_cnt,

@@ -2,7 +2,7 @@
 //
 // Work item = one (head, query block): 128 query rows against its selected key blocks.
 // A workgroup has 8 wavefronts = two GROUPS of 4; each group owns one work item (the two
-// query frames of the same spatial tile, which share their window), its own K and V tile
+// query blocks of the same spatial tile, which share their window), its own K and V tile
 // buffers in LDS, and wavefront w of a group owns query rows 32w .. 32w+31.
 //
 // Per selected key block a group runs three stages
@@ -131,13 +131,13 @@ __global__ __launch_bounds__(512, 2) void attn_mfma_kernel(
     const int wave = __builtin_amdgcn_readfirstlane((tid >> 6) & 3);  // wavefront within the group
     unsigned char *k_lds = lds_all[grp8][0], *v_lds = lds_all[grp8][1];
     const int ql = lane & 31, half = lane >> 5;
-    const int n_qb = g.q_frames * g.nb;
+    const int n_qb = g.q_groups * g.nb;
 
     // this group's item, and how many blocks the other group has (the stage clock is shared)
     auto item_row = [&](int item, int &head, int &qb) {
         head = item / n_qb;
         const int rem = item - head * n_qb;
-        const int tile = rem / g.q_frames, fq = rem - tile * g.q_frames;   // items ordered (head, tile, frame)
+        const int tile = rem / g.q_groups, fq = rem - tile * g.q_groups;   // items ordered (head, tile, group)
         qb = fq * g.nb + tile;
     };
     const int item = 2 * pair + grp8, other = 2 * pair + (grp8 ^ 1);
@@ -160,17 +160,18 @@ __global__ __launch_bounds__(512, 2) void attn_mfma_kernel(
     // (four small numbers packed into one register; they are only unpacked for clipped tiles)
     uint32_t key_rc;
     {
-        const int kr0 = lane / g.tw, kc0 = lane - kr0 * g.tw;
-        const int kr1 = (lane + 64) / g.tw, kc1 = (lane + 64) - kr1 * g.tw;
+        int ft, kr0, kc0, kr1, kc1;
+        block_token(g, lane, g.th, g.tw, ft, kr0, kc0);
+        block_token(g, lane + 64, g.th, g.tw, ft, kr1, kc1);
         key_rc = (uint32_t)kr0 | ((uint32_t)kc0 << 8) | ((uint32_t)kr1 << 16) | ((uint32_t)kc1 << 24);
     }
 
     // ---- Q fragments (B operand of S^T = K Q^T): lane holds query ql of this wavefront, channels 16s+8*half..+8
     const int tq = wave * 32 + ql;
-    const int qr = tq / g.tw, qc = tq - qr * g.tw;
-    const bool q_valid = active && qr < qvh && qc < qvw;
-    const int64_t token = q_valid ? ((int64_t)fq * g.H + by * g.th + qr) * g.W + bx * g.tw + qc
-                                  : ((int64_t)fq * g.H + by * g.th) * g.W + bx * g.tw;   // clamp padding rows
+    int qft, qr, qc;
+    const bool q_valid = block_token(g, tq, qvh, qvw, qft, qr, qc) && active;
+    const int64_t token = q_valid ? raster_token(g, fq, qft, by * g.th + qr, bx * g.tw + qc)
+                                  : raster_token(g, fq, 0, by * g.th, bx * g.tw);       // clamp padding rows
     bf16x8 bq[8];
     {
         const __bf16 *qp = q + token * q_st + (int64_t)head * q_sh + half * 8;
@@ -403,9 +404,9 @@ __global__ __launch_bounds__(512, 2) void attn_mfma_kernel(
 #pragma unroll
         for (int itr = 0; itr < 8; ++itr) {
             const int t = wave * 32 + rg + 4 * itr;
-            const int r = t / g.tw, cc = t - r * g.tw;
-            if (r < qvh && cc < qvw) {
-                const int64_t tok = ((int64_t)fq * g.H + by * g.th + r) * g.W + bx * g.tw + cc;
+            int ft, r, cc;
+            if (block_token(g, t, qvh, qvw, ft, r, cc)) {
+                const int64_t tok = raster_token(g, fq, ft, by * g.th + r, bx * g.tw + cc);
                 const uint4 u = *(const uint4 *)(k_lds + t * 256 + ((j ^ (t & 15)) << 4));
                 *(uint4 *)(o + tok * o_st + (int64_t)head * o_sh + j * 8) = u;
             }
@@ -418,7 +419,7 @@ __global__ __launch_bounds__(512, 2) void attn_mfma_kernel(
 hipError_t launch_attn_mfma(const KGeom &g, const KCache &c, const void *q, int64_t q_st, int64_t q_sh,
                             const int32_t *sel_idx, const int32_t *sel_cnt,
                             void *o, int64_t o_st, int64_t o_sh, float *lse, float scale, hipStream_t stream) {
-    const int total = g.heads * g.nb * g.q_frames;
+    const int total = g.heads * g.nb * g.q_groups;
     const int pairs = (total + 1) / 2;
     const int per_xcd = (pairs + 7) / 8;
     attn_mfma_kernel<<<dim3(per_xcd * 8), 512, 0, stream>>>(g, c, (const __bf16 *)q, q_st, q_sh, sel_idx, sel_cnt,

@@ -33,9 +33,10 @@ bool geom_ok(const lcsa_geom *g) {
     if (g->dtype != LCSA_F32 && g->dtype != LCSA_BF16) return false;
     const int vec = g->dtype == LCSA_BF16 ? 8 : 4;
     if (g->heads < 1 || g->head_dim < 1 || g->head_dim > 256 || g->head_dim % vec) return false;
-    if (g->grid_h < 1 || g->grid_w < 1 || g->tile_h < 1 || g->tile_w < 1) return false;
-    if ((int64_t)g->tile_h * g->tile_w > 1024) return false;
+    if (g->grid_h < 1 || g->grid_w < 1 || g->tile_h < 1 || g->tile_w < 1 || g->tile_t < 1) return false;
+    if ((int64_t)g->tile_h * g->tile_w * g->tile_t > 1024) return false;
     if (g->q_frames < 1 || g->cache_frames < g->q_frames) return false;
+    if (g->q_frames % g->tile_t || g->cache_frames % g->tile_t) return false;
     if (g->window_mode != LCSA_WINDOW_TRUNCATED && g->window_mode != LCSA_WINDOW_PRESERVED) return false;
     if (g->topk < 1) return false;
     // index arithmetic in the kernels is 32-bit for block ids and 64-bit for elements
@@ -48,12 +49,13 @@ bool geom_ok(const lcsa_geom *g) {
 KGeom derive(const lcsa_geom &g) {
     KGeom k;
     k.heads = g.heads; k.d = g.head_dim;
-    k.H = g.grid_h; k.W = g.grid_w; k.th = g.tile_h; k.tw = g.tile_w;
+    k.H = g.grid_h; k.W = g.grid_w; k.tt = g.tile_t; k.th = g.tile_h; k.tw = g.tile_w;
     k.ty = (g.grid_h + g.tile_h - 1) / g.tile_h;
     k.tx = (g.grid_w + g.tile_w - 1) / g.tile_w;
     k.nb = k.ty * k.tx;
-    k.bt = g.tile_h * g.tile_w;
-    k.q_frames = g.q_frames; k.cap = g.cache_frames;
+    k.ts = g.tile_h * g.tile_w;
+    k.bt = k.ts * g.tile_t;
+    k.q_groups = g.q_frames / g.tile_t; k.cap = g.cache_frames / g.tile_t;
     k.rh = g.radius_h; k.rw = g.radius_w; k.wmode = g.window_mode;
     k.topk = g.topk;
     k.bf16 = g.dtype == LCSA_BF16;
@@ -62,7 +64,7 @@ KGeom derive(const lcsa_geom &g) {
 
 bool same_geom(const lcsa_geom *a, const lcsa_geom &b) {
     return a->heads == b.heads && a->head_dim == b.head_dim && a->grid_h == b.grid_h && a->grid_w == b.grid_w &&
-           a->tile_h == b.tile_h && a->tile_w == b.tile_w && a->q_frames == b.q_frames &&
+           a->tile_h == b.tile_h && a->tile_w == b.tile_w && a->tile_t == b.tile_t && a->q_frames == b.q_frames &&
            a->cache_frames == b.cache_frames && a->dtype == b.dtype;
 }
 
@@ -127,49 +129,50 @@ int32_t lcsa_cache_reset(lcsa_cache *cache) {
 void lcsa_cache_free(lcsa_cache *cache) { delete cache; }
 
 int32_t lcsa_cache_valid_frames(const lcsa_cache *cache) {
-    return cache ? cache->kc.valid : (int32_t)LCSA_EINVAL;
+    return cache ? cache->kc.valid * cache->kg.tt : (int32_t)LCSA_EINVAL;
 }
 
 const float *lcsa_cache_pooled_k_device(const lcsa_cache *cache) { return cache ? cache->kc.pooled : nullptr; }
 
 int32_t lcsa_cache_frame_slot(const lcsa_cache *cache, int32_t frame) {
-    if (!cache || frame < 0 || frame >= cache->kc.valid) return LCSA_EINVAL;
-    return slot_of_frame(cache->kc.start, cache->kg.cap, frame);
+    if (!cache || frame < 0 || frame >= cache->kc.valid * cache->kg.tt) return LCSA_EINVAL;
+    return slot_of_frame(cache->kc.start, cache->kg.cap, frame / cache->kg.tt);
 }
 
 int32_t lcsa_kv_cache_append(lcsa_cache *cache, const void *k, const void *v,
                              int64_t stride_tok, int64_t stride_head, int32_t n_frames, void *stream) {
     if (!cache) return LCSA_EINVAL;
     const KGeom &kg = cache->kg;
-    if (n_frames < 1 || n_frames > kg.cap) return LCSA_EINVAL;
+    if (n_frames < 1 || n_frames % kg.tt || n_frames / kg.tt > kg.cap) return LCSA_EINVAL;
     if (!tensor_ok(k, stride_tok, stride_head, kg) || !tensor_ok(v, stride_tok, stride_head, kg)) return LCSA_EINVAL;
-    KCache &kc = cache->kc;
     if ((int64_t)n_frames * kg.H * kg.W > (1ll << 30)) return LCSA_EINVAL;
-    // New frames go into the slots right after the newest frame; once the ring is full
-    // those are the slots of the oldest frames, which thereby leave the window.
+    KCache &kc = cache->kc;
+    const int n_groups = n_frames / kg.tt;
+    // New groups go into the slots right after the newest one; once the ring is full those are the
+    // slots of the oldest groups, which thereby leave the window.
     const int first = slot_of_frame(kc.start, kg.cap, kc.valid);   // start + valid < 2*cap
-    hipError_t e = launch_append(kg, kc, k, v, stride_tok, stride_head, n_frames, first, (hipStream_t)stream);
+    hipError_t e = launch_append(kg, kc, k, v, stride_tok, stride_head, n_groups, first, (hipStream_t)stream);
     if (e != hipSuccess) return hip_status(e);
-    const int evict = kc.valid + n_frames > kg.cap ? kc.valid + n_frames - kg.cap : 0;
+    const int evict = kc.valid + n_groups > kg.cap ? kc.valid + n_groups - kg.cap : 0;
     kc.start = slot_of_frame(kc.start, kg.cap, evict);
-    kc.valid = kc.valid + n_frames - evict;
+    kc.valid = kc.valid + n_groups - evict;
     return LCSA_OK;
 }
 
 int32_t lcsa_pool_blocks(const lcsa_geom *geom, const void *x, int64_t stride_tok, int64_t stride_head,
                          int32_t n_frames, float *pooled, void *stream) {
-    if (!geom_ok(geom) || !pooled || n_frames < 1) return LCSA_EINVAL;
+    if (!geom_ok(geom) || !pooled || n_frames < 1 || n_frames % geom->tile_t) return LCSA_EINVAL;
     KGeom kg = derive(*geom);
     if (!tensor_ok(x, stride_tok, stride_head, kg)) return LCSA_EINVAL;
     if ((int64_t)n_frames * kg.H * kg.W > (1ll << 30)) return LCSA_EINVAL;
-    return hip_status(launch_pool(kg, x, stride_tok, stride_head, n_frames, pooled, (hipStream_t)stream));
+    return hip_status(launch_pool(kg, x, stride_tok, stride_head, n_frames / kg.tt, pooled, (hipStream_t)stream));
 }
 
 int32_t lcsa_select_blocks(const lcsa_geom *geom, const float *pooled_q, const lcsa_cache *cache,
                            int32_t *sel_idx, int32_t *sel_cnt, float *gap, void *stream) {
     if (!geom_ok(geom) || !cache || !pooled_q || !sel_idx || !sel_cnt) return LCSA_EINVAL;
     if (!same_geom(geom, cache->geom)) return LCSA_EINVAL;
-    if (cache->kc.valid < geom->q_frames) return LCSA_EINVAL;
+    if (cache->kc.valid * geom->tile_t < geom->q_frames) return LCSA_EINVAL;
     KGeom kg = derive(*geom);   // window, top-k may differ from the cache's own copy
     const int mc = max_candidates(kg, cache->kc.valid);
     if (mc > 8192) return LCSA_EUNSUPPORTED;
@@ -182,7 +185,7 @@ int32_t lcsa_sparse_attn_fwd(const lcsa_geom *geom, const void *q, int64_t q_str
                              float *lse, float scale, void *stream) {
     if (!geom_ok(geom) || !cache || !sel_idx || !sel_cnt) return LCSA_EINVAL;
     if (!same_geom(geom, cache->geom)) return LCSA_EINVAL;
-    if (cache->kc.valid < geom->q_frames) return LCSA_EINVAL;
+    if (cache->kc.valid * geom->tile_t < geom->q_frames) return LCSA_EINVAL;
     KGeom kg = derive(*geom);
     if (!tensor_ok(q, q_stride_tok, q_stride_head, kg) || !tensor_ok(o, o_stride_tok, o_stride_head, kg))
         return LCSA_EINVAL;

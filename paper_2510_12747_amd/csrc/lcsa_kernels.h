@@ -9,19 +9,20 @@ namespace lcsa {
 struct KGeom {
     int heads, d;
     int H, W;          // token grid per frame
-    int th, tw;        // tile shape
-    int ty, tx, nb;    // tiles per frame: rows, cols, total
-    int bt;            // tokens per full tile = th*tw
-    int q_frames, cap; // chunk frames, ring capacity in frames
+    int tt, th, tw;    // block shape: frames x rows x cols
+    int ty, tx, nb;    // spatial tiles per frame: rows, cols, total (= blocks per group of tt frames)
+    int ts, bt;        // tokens per full spatial tile = th*tw, per full block = tt*ts
+    int q_groups, cap; // chunk length and ring capacity, both in groups of tt frames
     int rh, rw, wmode;
     int topk;
     int bf16;          // element type of Q,K,V,O and cache: 1 = bf16, 0 = f32
 };
 
 // Ring cache as the kernels see it.
-//   K tiles : [heads][cap][nb][tile image]   element type = geometry dtype
+//   K tiles : [heads][cap][nb][tile image]   element type = geometry dtype; cap ring slots, one per group
 //   V tiles : same extent
 //   pooled  : float [heads][cap*nb][d], indexed by ring slot
+// Tokens of a block are ordered (frame in group, tile row, tile col).
 // Tile image, generic layout: K and V row-major [bt][d], padded tokens zero.
 // Tile image, matrix-core layout (bf16, d = 128, bt = 128): 128 rows of 256 bytes,
 //   the 16-byte chunk j of row r stored at chunk position j ^ (r & 15);
@@ -30,8 +31,8 @@ struct KGeom {
 struct KCache {
     void *k, *v;
     float *pooled;
-    int start;   // ring slot of the oldest visible frame
-    int valid;   // visible frames
+    int start;   // ring slot of the oldest visible group
+    int valid;   // visible groups
     int mfma_layout;
 };
 
@@ -40,13 +41,27 @@ __host__ __device__ inline int slot_of_frame(int start, int cap, int f) {
     return s >= cap ? s - cap : s;
 }
 
+// Block token i -> (frame within the group, row, col inside the tile); true if it exists in a tile
+// clipped to vh x vw.
+__host__ __device__ inline bool block_token(const KGeom &g, int i, int vh, int vw, int &ft, int &r, int &c) {
+    ft = i / g.ts;
+    const int rem = i - ft * g.ts;
+    r = rem / g.tw;
+    c = rem - r * g.tw;
+    return i < g.bt && r < vh && c < vw;
+}
+// Raster token index of (group, frame in group, absolute row, absolute col).
+__host__ __device__ inline int64_t raster_token(const KGeom &g, int group, int ft, int row, int col) {
+    return ((int64_t)(group * g.tt + ft) * g.H + row) * g.W + col;
+}
+
 // Every launcher enqueues on `stream` and returns hipGetLastError().
 hipError_t launch_pool(const KGeom &g, const void *x, int64_t stride_tok, int64_t stride_head,
-                       int n_frames, float *pooled, hipStream_t stream);
+                       int n_groups, float *pooled, hipStream_t stream);
 
-// Writes frames into ring slots first_slot.. (mod cap): tiles of K, V and pooled K.
+// Writes n_groups groups of frames into ring slots first_slot.. (mod cap): tiles of K, V and pooled K.
 hipError_t launch_append(const KGeom &g, const KCache &c, const void *k, const void *v,
-                         int64_t stride_tok, int64_t stride_head, int n_frames, int first_slot,
+                         int64_t stride_tok, int64_t stride_head, int n_groups, int first_slot,
                          hipStream_t stream);
 
 hipError_t launch_select(const KGeom &g, const KCache &c, const float *pooled_q,
@@ -64,7 +79,7 @@ hipError_t launch_attn_mfma(const KGeom &g, const KCache &c, const void *q, int6
                             hipStream_t stream);
 
 // Largest number of admissible key blocks of any query block (host arithmetic).
-int max_candidates(const KGeom &g, int valid_frames);
+int max_candidates(const KGeom &g, int valid_groups);
 
 // Window of tile index b along one axis: [*lo, *hi).
 __host__ __device__ inline void axis_window(int b, int tile, int n, int radius, int mode, int *lo, int *hi) {

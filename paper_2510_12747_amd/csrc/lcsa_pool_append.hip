@@ -28,14 +28,14 @@ template <> struct Unpack<4> {   // 4 x f32
 };
 
 struct TileRef {
-    int frame, by, bx;   // frame within the call's tensor, tile coordinates
+    int group, by, bx;   // group of tt frames within the call's tensor, tile coordinates
     int vh, vw;          // valid rows / cols of the tile
 };
 
 __device__ inline TileRef tile_ref(const KGeom &g, int block) {
     TileRef t;
-    t.frame = block / g.nb;
-    int tile = block - t.frame * g.nb;
+    t.group = block / g.nb;
+    int tile = block - t.group * g.nb;
     t.by = tile / g.tx;
     t.bx = tile - t.by * g.tx;
     t.vh = min(g.th, g.H - t.by * g.th);
@@ -60,7 +60,7 @@ __device__ inline void finish_pool(float *red, const float *acc, int rg, int j, 
 }
 
 // ---------------------------------------------------------------------------------------------
-// pooled[head][block][c] = mean over the block's valid tokens.      grid (n_frames*nb, heads)
+// pooled[head][block][c] = mean over the block's valid tokens.      grid (n_groups*nb, heads)
 template <int VEC>
 __global__ __launch_bounds__(kThreads) void pool_kernel(KGeom g, const char *x, int64_t st, int64_t sh,
                                                         int n_blocks, float *pooled) {
@@ -82,10 +82,10 @@ __global__ __launch_bounds__(kThreads) void pool_kernel(KGeom g, const char *x, 
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
                 const int tok = tok0 + i * rows_par;
-                const int r = tok / g.tw, c = tok - r * g.tw;
+                int ft, r, c;
                 u[i] = make_uint4(0, 0, 0, 0);
-                if (tok < g.bt && r < t.vh && c < t.vw) {
-                    const int64_t token = ((int64_t)t.frame * g.H + t.by * g.th + r) * g.W + t.bx * g.tw + c;
+                if (block_token(g, tok, t.vh, t.vw, ft, r, c)) {
+                    const int64_t token = raster_token(g, t.group, ft, t.by * g.th + r, t.bx * g.tw + c);
                     u[i] = *(const uint4 *)(x + (token * st + (int64_t)head * sh + j * VEC) * ELT);
                 }
             }
@@ -98,22 +98,21 @@ __global__ __launch_bounds__(kThreads) void pool_kernel(KGeom g, const char *x, 
             }
         }
     }
-    finish_pool<VEC>(red, acc, rg, j, lpr, rows_par, active, g.d, t.vh * t.vw,
+    finish_pool<VEC>(red, acc, rg, j, lpr, rows_par, active, g.d, g.tt * t.vh * t.vw,
                      pooled + ((int64_t)head * n_blocks + block) * g.d);
 }
 
 // ---------------------------------------------------------------------------------------------
 // Cache append, generic tile image: K and V tiles row-major [bt][d], padded tokens zero;
-// pooled K written beside them.                                      grid (n_frames*nb, heads)
+// pooled K written beside them.                                      grid (n_groups*nb, heads)
 template <int VEC>
 __global__ __launch_bounds__(kThreads) void append_generic_kernel(KGeom g, KCache c, const char *k, const char *v,
                                                                   int64_t st, int64_t sh, int first_slot) {
     __shared__ float red[kThreads * VEC];
     const int block = blockIdx.x, head = blockIdx.y;
     const TileRef t = tile_ref(g, block);
-    int slot = first_slot + t.frame;
-    slot = slot % g.cap;
-    const int tile = block - t.frame * g.nb;
+    const int slot = (first_slot + t.group) % g.cap;
+    const int tile = block - t.group * g.nb;
     constexpr int ELT = 16 / VEC;
     const int64_t tile_index = ((int64_t)head * g.cap + slot) * g.nb + tile;
     char *kt = (char *)c.k + tile_index * g.bt * g.d * ELT;
@@ -126,11 +125,11 @@ __global__ __launch_bounds__(kThreads) void append_generic_kernel(KGeom g, KCach
     for (int e = 0; e < VEC; ++e) acc[e] = 0.f;
     if (active) {
         for (int tok = rg; tok < g.bt; tok += rows_par) {
-            int r = tok / g.tw, cc = tok - r * g.tw;
+            int ft, r, cc;
             uint4 uk = make_uint4(0, 0, 0, 0), uv = uk;
-            if (r < t.vh && cc < t.vw) {
-                int64_t token = ((int64_t)t.frame * g.H + t.by * g.th + r) * g.W + t.bx * g.tw + cc;
-                int64_t off = (token * st + (int64_t)head * sh + j * VEC) * ELT;
+            if (block_token(g, tok, t.vh, t.vw, ft, r, cc)) {
+                const int64_t token = raster_token(g, t.group, ft, t.by * g.th + r, t.bx * g.tw + cc);
+                const int64_t off = (token * st + (int64_t)head * sh + j * VEC) * ELT;
                 uk = *(const uint4 *)(k + off);
                 uv = *(const uint4 *)(v + off);
                 float f[VEC];
@@ -142,7 +141,7 @@ __global__ __launch_bounds__(kThreads) void append_generic_kernel(KGeom g, KCach
             *(uint4 *)(vt + ((int64_t)tok * g.d + j * VEC) * ELT) = uv;
         }
     }
-    finish_pool<VEC>(red, acc, rg, j, lpr, rows_par, active, g.d, t.vh * t.vw,
+    finish_pool<VEC>(red, acc, rg, j, lpr, rows_par, active, g.d, g.tt * t.vh * t.vw,
                      c.pooled + tile_index * g.d);
 }
 
@@ -164,7 +163,7 @@ __device__ inline uint32_t bf16_bits_to_half_bits(uint32_t b) {
 // magnitude in [2^-14, 65504] converts exactly (8 significant bits into 11), smaller ones round
 // to half subnormals (absolute error < 2^-25), larger ones saturate to +-65504.  Half is what the
 // second matrix product runs in, because softmax probabilities need mantissa, not range.
-//                                                                    grid (n_frames*nb, heads)
+//                                                                    grid (n_groups*nb, heads)
 constexpr int kVPitchWords = 65;   // LDS pitch of a staged V token row (128 bf16 = 64 words, +1)
 
 __global__ __launch_bounds__(kThreads) void append_mfma_kernel(KGeom g, KCache c, const char *k, const char *v,
@@ -173,8 +172,8 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(KGeom g, KCache c
     __shared__ uint32_t vs[128 * kVPitchWords];
     const int block = blockIdx.x, head = blockIdx.y;
     const TileRef t = tile_ref(g, block);
-    const int slot = (first_slot + t.frame) % g.cap;
-    const int tile = block - t.frame * g.nb;
+    const int slot = (first_slot + t.group) % g.cap;
+    const int tile = block - t.group * g.nb;
     const int64_t tile_index = ((int64_t)head * g.cap + slot) * g.nb + tile;
     char *kt = (char *)c.k + tile_index * (128 * 256);
     char *vt = (char *)c.v + tile_index * (128 * 256);
@@ -185,11 +184,11 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(KGeom g, KCache c
 #pragma unroll
     for (int it = 0; it < 8; ++it) {
         const int tok = rg + 16 * it;
-        const int r = tok / g.tw, cc = tok - r * g.tw;
+        int ft, r, cc;
         uint4 uk = make_uint4(0, 0, 0, 0), uv = uk;
-        if (r < t.vh && cc < t.vw) {
-            int64_t token = ((int64_t)t.frame * g.H + t.by * g.th + r) * g.W + t.bx * g.tw + cc;
-            int64_t off = (token * st + (int64_t)head * sh + j * 8) * 2;
+        if (block_token(g, tok, t.vh, t.vw, ft, r, cc)) {
+            const int64_t token = raster_token(g, t.group, ft, t.by * g.th + r, t.bx * g.tw + cc);
+            const int64_t off = (token * st + (int64_t)head * sh + j * 8) * 2;
             uk = *(const uint4 *)(k + off);
             uv = *(const uint4 *)(v + off);
             float f[8];
@@ -217,25 +216,25 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(KGeom g, KCache c
         }
         *(uint4 *)(vt + dd * 256 + (pos << 4)) = make_uint4(w[0], w[1], w[2], w[3]);
     }
-    finish_pool<8>(red, acc, rg, j, 16, 16, true, 128, t.vh * t.vw, c.pooled + tile_index * 128);
+    finish_pool<8>(red, acc, rg, j, 16, 16, true, 128, g.tt * t.vh * t.vw, c.pooled + tile_index * 128);
 }
 
 } // namespace
 
 hipError_t launch_pool(const KGeom &g, const void *x, int64_t stride_tok, int64_t stride_head,
-                       int n_frames, float *pooled, hipStream_t stream) {
-    dim3 grid(n_frames * g.nb, g.heads);
+                       int n_groups, float *pooled, hipStream_t stream) {
+    dim3 grid(n_groups * g.nb, g.heads);
     if (g.bf16)
-        pool_kernel<8><<<grid, kThreads, 0, stream>>>(g, (const char *)x, stride_tok, stride_head, n_frames * g.nb, pooled);
+        pool_kernel<8><<<grid, kThreads, 0, stream>>>(g, (const char *)x, stride_tok, stride_head, n_groups * g.nb, pooled);
     else
-        pool_kernel<4><<<grid, kThreads, 0, stream>>>(g, (const char *)x, stride_tok, stride_head, n_frames * g.nb, pooled);
+        pool_kernel<4><<<grid, kThreads, 0, stream>>>(g, (const char *)x, stride_tok, stride_head, n_groups * g.nb, pooled);
     return hipGetLastError();
 }
 
 hipError_t launch_append(const KGeom &g, const KCache &c, const void *k, const void *v,
-                         int64_t stride_tok, int64_t stride_head, int n_frames, int first_slot,
+                         int64_t stride_tok, int64_t stride_head, int n_groups, int first_slot,
                          hipStream_t stream) {
-    dim3 grid(n_frames * g.nb, g.heads);
+    dim3 grid(n_groups * g.nb, g.heads);
     if (c.mfma_layout)
         append_mfma_kernel<<<grid, kThreads, 0, stream>>>(g, c, (const char *)k, (const char *)v, stride_tok, stride_head, first_slot);
     else if (g.bf16)

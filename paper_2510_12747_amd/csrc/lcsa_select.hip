@@ -28,7 +28,7 @@ __global__ __launch_bounds__(64) void select_kernel(KGeom g, KCache c, const flo
     float *qs = smem;                                  // [d] pooled query of this row
     uint32_t *keys = (uint32_t *)(smem + g.d);         // [n] ordered keys of the admissible blocks
     const int qb = blockIdx.x, head = blockIdx.y, lane = threadIdx.x;
-    const int n_qb = g.q_frames * g.nb;
+    const int n_qb = g.q_groups * g.nb;
     const int tile = qb % g.nb, by = tile / g.tx, bx = tile - by * g.tx;
     int y0, y1, x0, x1;
     axis_window(by, g.th, g.ty, g.rh, g.wmode, &y0, &y1);
@@ -40,7 +40,7 @@ __global__ __launch_bounds__(64) void select_kernel(KGeom g, KCache c, const flo
     for (int i = lane; i < g.d; i += 64) qs[i] = pooled_q[row * g.d + i];
     __syncthreads();
 
-    // candidate ci -> (visible frame f, tile t); key-block id = f*nb + t grows with ci
+    // candidate ci -> (visible group f, tile t); key-block id = f*nb + t grows with ci
     auto tile_of = [&](int ci, int &f) {
         f = ci / nwin;
         int w = ci - f * nwin, wy = w / wx;
@@ -139,16 +139,16 @@ __global__ __launch_bounds__(64) void select_kernel(KGeom g, KCache c, const flo
 
 } // namespace
 
-int max_candidates(const KGeom &g, int valid_frames) {
+int max_candidates(const KGeom &g, int valid_groups) {
     int my = 0, mx = 0;
     for (int b = 0; b < g.ty; ++b) { int lo, hi; axis_window(b, g.th, g.ty, g.rh, g.wmode, &lo, &hi); if (hi - lo > my) my = hi - lo; }
     for (int b = 0; b < g.tx; ++b) { int lo, hi; axis_window(b, g.tw, g.tx, g.rw, g.wmode, &lo, &hi); if (hi - lo > mx) mx = hi - lo; }
-    return my * mx * valid_frames;
+    return my * mx * valid_groups;
 }
 
 hipError_t launch_select(const KGeom &g, const KCache &c, const float *pooled_q,
                          int32_t *sel_idx, int32_t *sel_cnt, float *gap, int max_cand, hipStream_t stream) {
-    dim3 grid(g.q_frames * g.nb, g.heads);
+    dim3 grid(g.q_groups * g.nb, g.heads);
     const size_t lds = (size_t)(g.d + max_cand) * sizeof(float);
     select_kernel<<<grid, 64, lds, stream>>>(g, c, pooled_q, sel_idx, sel_cnt, gap);
     return hipGetLastError();

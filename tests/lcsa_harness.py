@@ -34,15 +34,16 @@ def to_device(x: np.ndarray, dtype: str, layout: str = "thd") -> torch.Tensor:
     return t.cuda()
 
 
-def geoms(w: wl.Workload, topk=None, radius=None, window_mode=0):
+def geoms(w: wl.Workload, topk=None, radius=None, window_mode=0, tile_t=1):
     """(library geometry, oracle geometry) of a workload."""
     k = w.topk if topk is None else topk
     r = w.radius if radius is None else radius
     rh, rw = (r, r) if np.isscalar(r) else r
     g = B.Geom(w.heads, w.head_dim, w.grid_h, w.grid_w, w.tile_h, w.tile_w, w.q_frames, w.cache_frames,
-               rh, rw, k, dtype=B.LCSA_BF16 if w.dtype == "bf16" else B.LCSA_F32, window_mode=window_mode)
+               rh, rw, k, dtype=B.LCSA_BF16 if w.dtype == "bf16" else B.LCSA_F32, window_mode=window_mode,
+               tile_t=tile_t)
     og = oracle.Geometry(w.heads, w.head_dim, w.grid_h, w.grid_w, w.tile_h, w.tile_w, w.q_frames, rh, rw, k,
-                         window_mode=window_mode)
+                         window_mode=window_mode, tile_t=tile_t)
     return g, og
 
 
@@ -53,10 +54,11 @@ def sample_rows(og: oracle.Geometry, n_random: int, seed: int = 0) -> np.ndarray
     tx = -(-og.grid_w // og.tile_w)
     nb = ty * tx
     tiles = {(by, bx) for by in (0, ty // 2, ty - 1) for bx in (0, tx // 2, tx - 1)}
-    rows = {(h, f * nb + by * tx + bx) for h in {0, og.heads - 1} for f in range(og.q_frames) for by, bx in tiles}
+    q_groups = og.q_frames // og.tile_t
+    rows = {(h, f * nb + by * tx + bx) for h in {0, og.heads - 1} for f in range(q_groups) for by, bx in tiles}
     rng = np.random.default_rng(seed)
-    while len(rows) < len(tiles) * og.q_frames * len({0, og.heads - 1}) + n_random:
-        rows.add((int(rng.integers(og.heads)), int(rng.integers(og.q_frames * nb))))
+    while len(rows) < len(tiles) * q_groups * len({0, og.heads - 1}) + n_random:
+        rows.add((int(rng.integers(og.heads)), int(rng.integers(q_groups * nb))))
     return np.array(sorted(rows), np.int32)
 
 
@@ -82,7 +84,7 @@ def check_selection(sel_idx, sel_cnt, o_idx, o_cnt, o_gap, og, kv_frames):
         m = sel_cnt[h, qb]
         kept = sel_idx[h, qb, :m]
         assert (np.diff(kept) > 0).all() and (sel_idx[h, qb, m:] == -1).all()
-        assert all(oracle.allowed(int(qb), int(kb), og) for kb in kept) and kept.max() < kv_frames * og.nb
+        assert all(oracle.allowed(int(qb), int(kb), og) for kb in kept) and kept.max() < kv_frames // og.tile_t * og.nb
     return sel_idx, sel_cnt, int(diff.sum()), int(near.sum())
 
 
@@ -127,10 +129,10 @@ class Pipeline:
         K, _ = self.model.visible()
         want = oracle.pool(K, self.og, self.model.valid_frames)
         got = B.lcsa_cache_pooled_k(self.cache).cpu().numpy()
-        nb = self.g.nb
-        for f in range(self.model.valid_frames):
-            s = B.lcsa_cache_frame_slot(self.cache, f)
-            np.testing.assert_allclose(got[:, s * nb:(s + 1) * nb], want[:, f * nb:(f + 1) * nb], rtol=0, atol=tol)
+        nb, tt = self.g.nb, self.g.tile_t
+        for grp in range(self.model.valid_frames // tt):
+            s = B.lcsa_cache_frame_slot(self.cache, grp * tt)
+            np.testing.assert_allclose(got[:, s * nb:(s + 1) * nb], want[:, grp * nb:(grp + 1) * nb], rtol=0, atol=tol)
 
     def step(self, q, qd, rows=None, g=None, og=None, scale=0.0, max_abs=OUT_MAX_ABS, mean_abs=OUT_MEAN_ABS,
              check_lse=False) -> StepResult:
@@ -158,5 +160,5 @@ class Pipeline:
             _, want_lse = oracle.attend(q, K, V, og, kvf, s_idx, s_cnt, scale=scale, rows=rows, with_lse=True)
             done = ~np.isnan(want_lse)
             np.testing.assert_allclose(lse.cpu().numpy()[done], want_lse[done], rtol=0, atol=2e-3)
-        n_rows = g.heads * g.q_frames * g.nb if rows is None else len(rows)
+        n_rows = g.heads * g.n_qb if rows is None else len(rows)
         return StepResult(n_diff, n_near, mx, mean, n_rows)

@@ -44,11 +44,15 @@ def test_cache_bytes_formula():
     assert B.lcsa_cache_device_bytes(g) == 2 * tiles * 128 * 128 * 2 + tiles * 128 * 4
     tiny = B.Geom(1, 32, 6, 8, 4, 4, 2, 4, 4, 4, 4, dtype=B.LCSA_F32)
     assert B.lcsa_cache_device_bytes(tiny) == 2 * (16 * 16 * 32 * 4) + 16 * 32 * 4
+    # (2,8,8) blocks on the paper grid: 66 blocks per frame pair, 3 pairs in the ring, 128 tokens per block
+    paper288 = B.Geom(**{**PAPER, "tile_w": 8, "tile_t": 2})
+    assert paper288.nb == 66 and paper288.n_qb == 66
+    assert B.lcsa_cache_device_bytes(paper288) == 2 * (12 * 3 * 66) * 128 * 128 * 2 + (12 * 3 * 66) * 128 * 4
 
 
 @pytest.mark.parametrize("field,value", [
     ("heads", 0), ("head_dim", 0), ("head_dim", 12), ("head_dim", 264), ("grid_h", 0), ("tile_w", 0),
-    ("q_frames", 0), ("cache_frames", 1), ("topk", 0), ("dtype", 2), ("window_mode", 3),
+    ("q_frames", 0), ("cache_frames", 1), ("topk", 0), ("dtype", 2), ("window_mode", 3), ("tile_t", 0), ("tile_t", 4),
 ])
 def test_invalid_geometry_is_rejected(field, value):
     g = B.Geom(**{**PAPER, field: value})

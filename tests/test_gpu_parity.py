@@ -280,3 +280,36 @@ def test_more_than_64_selected_blocks_refills_the_id_chunk():
     w = wl.with_overrides(wl.WORKLOADS["small"], name="refill", heads=1, grid_h=40, grid_w=48, radius=-1, topk=128)
     p, r = run_primed(w, check_lse=True)
     assert r.rows_checked == 30
+
+
+# ---- the paper's own block shape: (2, 8, 8) = two frames x 8 x 8 tokens (Sec. 3.2) ----------------------
+
+def test_paper_block_shape_2x8x8_small_grid_all_rows():
+    w = wl.with_overrides(wl.WORKLOADS["small"], name="blocks-2x8x8", heads=3, tile_h=8, tile_w=8)
+    say("24x44 grid, (2,8,8) blocks: 18 blocks per frame pair, last tile column 4 wide; matrix-core path")
+    p, r = run_primed(w, tile_t=2, check_lse=True)
+    assert p.g.n_qb == 18 and r.rows_checked == 3 * 18
+    run_primed(w, tile_t=2, window_mode=1, topk=5)
+
+
+def test_paper_block_shape_2x8x8_paper_scale_sampled_rows():
+    """48x88 grid with (2,8,8) blocks tiles exactly: 66 blocks per two-frame chunk, 198 key blocks."""
+    w = wl.with_overrides(wl.WORKLOADS["paper"], name="paper-2x8x8", tile_h=8, tile_w=8)
+    g, og = geoms(w, tile_t=2)
+    assert g.nb == 66 and g.n_qb == 66
+    run_primed(w, rows=sample_rows(og, 40), tile_t=2)
+
+
+def test_temporal_blocks_generic_f32():
+    w = wl.with_overrides(wl.WORKLOADS["tiny"], name="tiny-2x4x4", heads=2, grid_h=10, grid_w=14, radius=4, topk=3)
+    say("f32 generic path, (2,4,4) blocks on a 10x14 grid")
+    run_primed(w, tile_t=2, check_lse=True)
+
+
+def test_temporal_blocks_reject_odd_frame_counts():
+    g = B.Geom(2, 128, 16, 16, 8, 8, 2, 6, 8, 8, 4, tile_t=2)
+    cache = B.lcsa_cache_init(g)
+    k = torch.zeros(256, 2, 128, dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(B.LcsaError):
+        B.lcsa_kv_cache_append(cache, k, k, 1)                       # one frame into two-frame blocks
+    assert B.lcsa_cache_device_bytes(B.Geom(2, 128, 16, 16, 8, 8, 3, 6, 8, 8, 4, tile_t=2)) == 0   # q_frames not a multiple
