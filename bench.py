@@ -206,7 +206,7 @@ def main() -> int:
                     "pool_blocks": round(pool_bytes / (brk[1] * 1e-3) / 1e9, 1)},
         "roofline": {"kernel": "attn_mfma_kernel", "bound": "mfma", "achieved": round(achieved, 2),
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
-                     "traffic": ATTN_TRAFFIC_BYTES.get((args.workload, topk)),
+                     "traffic": ATTN_TRAFFIC_BYTES.get((args.workload, topk)) if not args.blocks and args.radius is None else None,
                      "flop_per_launch_useful": useful_flop, "flop_per_launch_issued": issued_flop,
                      "issued_tflops": round(issued_flop / (attn_avg_ms * 1e-3) / 1e12, 2),
                      "avg_launch_ms": round(attn_avg_ms, 5), "min_launch_ms": round(float(attn_ms.min()), 5)},

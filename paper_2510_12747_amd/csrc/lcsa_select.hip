@@ -1,9 +1,9 @@
 // Block selection: coarse block-to-block scores (Sec. 3.2) restricted to the spatial local
 // window (Sec. 3.3, Fig. 3), then the per-row top-k with ties going to the lower key-block
-// id.  One wavefront owns one (head, query block) row: lanes stride over the admissible key
-// blocks for the dot products, the k-th largest score is found by a 32-step bitwise search
-// over order-preserving integer keys with ballot/popcount, and the kept ids are emitted in
-// ascending order with ballot prefix counts.  No sort, no atomics, fully deterministic.
+// id.  One workgroup owns one (head, query block) row: four lanes share each dot product
+// against an admissible key block, then one wavefront finds the k-th largest score by a 32-step
+// bitwise search over order-preserving integer keys with ballot/popcount and emits the kept ids
+// in ascending order with ballot prefix counts.  No sort, no atomics, fully deterministic.
 #include "lcsa_kernels.h"
 
 namespace lcsa {
@@ -21,13 +21,15 @@ __device__ inline float key_to_float(uint32_t key) {
 
 __device__ inline int wave_count(bool p) { return __popcll(__ballot(p)); }
 
-__global__ __launch_bounds__(64) void select_kernel(KGeom g, KCache c, const float *__restrict__ pooled_q,
-                                                    int32_t *__restrict__ sel_idx, int32_t *__restrict__ sel_cnt,
-                                                    float *__restrict__ gap) {
+constexpr int kSelThreads = 256;
+
+__global__ __launch_bounds__(kSelThreads) void select_kernel(KGeom g, KCache c, const float *__restrict__ pooled_q,
+                                                             int32_t *__restrict__ sel_idx, int32_t *__restrict__ sel_cnt,
+                                                             float *__restrict__ gap) {
     extern __shared__ float smem[];
     float *qs = smem;                                  // [d] pooled query of this row
     uint32_t *keys = (uint32_t *)(smem + g.d);         // [n] ordered keys of the admissible blocks
-    const int qb = blockIdx.x, head = blockIdx.y, lane = threadIdx.x;
+    const int qb = blockIdx.x, head = blockIdx.y, tid = threadIdx.x, lane = tid & 63;
     const int n_qb = g.q_groups * g.nb;
     const int tile = qb % g.nb, by = tile / g.tx, bx = tile - by * g.tx;
     int y0, y1, x0, x1;
@@ -37,7 +39,7 @@ __global__ __launch_bounds__(64) void select_kernel(KGeom g, KCache c, const flo
     const int n = c.valid * nwin;                      // admissible key blocks, in ascending id order
     const int64_t row = (int64_t)head * n_qb + qb;
 
-    for (int i = lane; i < g.d; i += 64) qs[i] = pooled_q[row * g.d + i];
+    for (int i = tid; i < g.d; i += kSelThreads) qs[i] = pooled_q[row * g.d + i];
     __syncthreads();
 
     // candidate ci -> (visible group f, tile t); key-block id = f*nb + t grows with ci
@@ -47,31 +49,39 @@ __global__ __launch_bounds__(64) void select_kernel(KGeom g, KCache c, const flo
         return (y0 + wy) * g.tx + x0 + (w - wy * wx);
     };
 
-    for (int ci = lane; ci < n; ci += 64) {
-        int f;
-        const int t = tile_of(ci, f);
-        const int slot = slot_of_frame(c.start, g.cap, f);
-        const float4 *kr = (const float4 *)(c.pooled + (((int64_t)head * g.cap + slot) * g.nb + t) * g.d);
-        float s = 0.f;
-        // the pooled-K row is fetched 16 float4 at a time so that the loads overlap instead of each
-        // FMA group waiting out one L2 round trip
-        const int n4 = g.d / 4;
-        for (int e0 = 0; e0 < n4; e0 += 16) {
-            float4 kk[16];
+    // ---- scores: four lanes per candidate, each a quarter of the channels (interleaved float4s so
+    // that the four lanes read one contiguous 64-byte piece at a time); all loads of a lane are
+    // issued before the first FMA
+    {
+        const int part = tid & 3, n4 = g.d / 4;
+        for (int ci = tid >> 2; ci < ((n + 63) & ~63); ci += kSelThreads / 4) {
+            float s = 0.f;
+            if (ci < n) {
+                int f;
+                const int t = tile_of(ci, f);
+                const int slot = slot_of_frame(c.start, g.cap, f);
+                const float4 *kr = (const float4 *)(c.pooled + (((int64_t)head * g.cap + slot) * g.nb + t) * g.d);
+                for (int e0 = part; e0 < n4; e0 += 4 * 16) {
+                    float4 kk[16];
 #pragma unroll
-            for (int u = 0; u < 16; ++u) kk[u] = e0 + u < n4 ? kr[e0 + u] : make_float4(0.f, 0.f, 0.f, 0.f);
+                    for (int u = 0; u < 16; ++u) kk[u] = e0 + 4 * u < n4 ? kr[e0 + 4 * u] : make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
-            for (int u = 0; u < 16; ++u) {
-                const int e = (e0 + u < n4 ? e0 + u : 0) * 4;
-                s = fmaf(qs[e], kk[u].x, s);
-                s = fmaf(qs[e + 1], kk[u].y, s);
-                s = fmaf(qs[e + 2], kk[u].z, s);
-                s = fmaf(qs[e + 3], kk[u].w, s);
+                    for (int u = 0; u < 16; ++u) {
+                        const int e = (e0 + 4 * u < n4 ? e0 + 4 * u : 0) * 4;
+                        s = fmaf(qs[e], kk[u].x, s);
+                        s = fmaf(qs[e + 1], kk[u].y, s);
+                        s = fmaf(qs[e + 2], kk[u].z, s);
+                        s = fmaf(qs[e + 3], kk[u].w, s);
+                    }
+                }
             }
+            s += __shfl_xor(s, 1);
+            s += __shfl_xor(s, 2);
+            if (ci < n && part == 0) keys[ci] = order_key(s);
         }
-        keys[ci] = order_key(s);
     }
     __syncthreads();
+    if (tid >= 64) return;                             // the selection itself is one wavefront's work
 
     int32_t *out = sel_idx + row * g.topk;
     const int k = g.topk;
@@ -86,16 +96,25 @@ __global__ __launch_bounds__(64) void select_kernel(KGeom g, KCache c, const flo
         }
         written = n;
     } else {
-        // T = k-th largest key: the largest value with at least k keys >= it
+        // T = k-th largest key: the largest value with at least k keys >= it (32-step bitwise search)
         uint32_t T = 0;
-        for (int bit = 31; bit >= 0; --bit) {
-            const uint32_t trial = T | (1u << bit);
-            int cnt = 0;
-            for (int base = 0; base < n; base += 64) {
-                const int ci = base + lane;
-                cnt += wave_count(ci < n && keys[ci] >= trial);
+        if (n <= 128) {
+            // the common case (a window of at most 21 tiles over 6 frames): two keys per lane in registers
+            const uint32_t k0 = lane < n ? keys[lane] : 0u, k1 = lane + 64 < n ? keys[lane + 64] : 0u;   // finite floats map to keys > 0
+            for (int bit = 31; bit >= 0; --bit) {
+                const uint32_t trial = T | (1u << bit);
+                if (wave_count(k0 >= trial) + wave_count(k1 >= trial) >= k) T = trial;
             }
-            if (cnt >= k) T = trial;
+        } else {
+            for (int bit = 31; bit >= 0; --bit) {
+                const uint32_t trial = T | (1u << bit);
+                int cnt = 0;
+                for (int base = 0; base < n; base += 64) {
+                    const int ci = base + lane;
+                    cnt += wave_count(ci < n && keys[ci] >= trial);
+                }
+                if (cnt >= k) T = trial;
+            }
         }
         int n_gt = 0, n_ge = 0;
         uint32_t below = 0;                              // largest key < T (0 if none; keys of finite floats are > 0)
@@ -150,7 +169,7 @@ hipError_t launch_select(const KGeom &g, const KCache &c, const float *pooled_q,
                          int32_t *sel_idx, int32_t *sel_cnt, float *gap, int max_cand, hipStream_t stream) {
     dim3 grid(g.q_groups * g.nb, g.heads);
     const size_t lds = (size_t)(g.d + max_cand) * sizeof(float);
-    select_kernel<<<grid, 64, lds, stream>>>(g, c, pooled_q, sel_idx, sel_cnt, gap);
+    select_kernel<<<grid, kSelThreads, lds, stream>>>(g, c, pooled_q, sel_idx, sel_cnt, gap);
     return hipGetLastError();
 }
 
