@@ -156,6 +156,18 @@ __global__ __launch_bounds__(512, 2) void attn_mfma_kernel(
     const int qvh = min(g.th, g.H - by * g.th), qvw = min(g.tw, g.W - bx * g.tw);
     const int ph = g.H - (g.ty - 1) * g.th, pw = g.W - (g.tx - 1) * g.tw;   // extent of clipped edge tiles
 
+    // ---- the first K tile is requested before anything else so that its latency overlaps the set-up
+    const char *k_head = (const char *)c.k + (int64_t)head * g.cap * g.nb * kTileBytes;
+    const char *v_head = (const char *)c.v + (int64_t)head * g.cap * g.nb * kTileBytes;
+    auto tile_off = [](uint32_t blk) { return (int64_t)(blk & 0xffffffu) * kTileBytes; };
+    const uint32_t copy_voff = wave * 8192 + lane * 16;     // this lane's byte offset inside any tile image
+    if (cnt > 0) {
+        const uint32_t blk0 = __builtin_amdgcn_readfirstlane(pack_block(g, c, sel[0], ph, pw));
+        const uint32_t kdst0 = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)((LCSA_LDS unsigned char *)k_lds) + wave * 8192);
+#pragma unroll
+        for (int piece = 0; piece < 8; ++piece) copy_piece_to_lds(k_head + tile_off(blk0), copy_voff, kdst0, piece);
+    }
+
     // tile-token coordinates of keys `lane` and `lane + 64`, for the validity ballots of clipped tiles
     // (four small numbers packed into one register; they are only unpacked for clipped tiles)
     uint32_t key_rc;
@@ -199,19 +211,8 @@ __global__ __launch_bounds__(512, 2) void attn_mfma_kernel(
         for (int i = 0; i < 16; ++i) oacc[dt][i] = 0.f;
     float m_run = -__builtin_inff(), l_run = 0.f;
 
-    const char *k_head = (const char *)c.k + (int64_t)head * g.cap * g.nb * kTileBytes;
-    const char *v_head = (const char *)c.v + (int64_t)head * g.cap * g.nb * kTileBytes;
-    auto tile_off = [](uint32_t blk) { return (int64_t)(blk & 0xffffffu) * kTileBytes; };
-
-    const uint32_t copy_voff = wave * 8192 + lane * 16;     // this lane's byte offset inside any tile image
     uint32_t blk = __builtin_amdgcn_readlane(blk_chunk, 0);
-    __builtin_amdgcn_s_waitcnt(0x0F70);    // vmcnt(0), visible to the compiler: Q fragments and ids are in registers
-    if (cnt > 0) {
-        const uint32_t kdst0 = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)((LCSA_LDS unsigned char *)k_lds) + wave * 8192);
-#pragma unroll
-        for (int piece = 0; piece < 8; ++piece) copy_piece_to_lds(k_head + tile_off(blk), copy_voff, kdst0, piece);
-    }
-    wait_vm0();
+    __builtin_amdgcn_s_waitcnt(0x0F70);    // vmcnt(0), visible to the compiler: Q fragments, ids and the first K tile have arrived
     stage_barrier();                       // first K tiles of both groups are in LDS
     if (grp8 == 1) { stage_barrier(); stage_barrier(); }   // group 1 runs two phases behind group 0
 
