@@ -49,6 +49,8 @@ def main() -> int:
     ap.add_argument("--topk", type=int, default=0, help="override top-k (a value >= the window size gives windowed dense attention)")
     ap.add_argument("--radius", type=int, default=None, help="override the locality radius in tokens (-1: unbounded window)")
     ap.add_argument("--blocks", default="", help="block shape t,h,w overriding the workload's 1,tile_h,tile_w (e.g. 2,8,8: the paper's partition)")
+    ap.add_argument("--grid", default="", help="latent grid h,w overriding the workload's (e.g. 96,168: a 1536x2688 video)")
+    ap.add_argument("--cache-frames", type=int, default=0, help="override the sliding-window capacity in frames")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device-to-device copy (reference point for HBM byte counters)")
@@ -74,6 +76,11 @@ def main() -> int:
     if args.blocks:
         tile_t, th, tw = (int(x) for x in args.blocks.split(","))
         w = wl.with_overrides(w, tile_h=th, tile_w=tw)
+    if args.grid:
+        gh, gw = (int(x) for x in args.grid.split(","))
+        w = wl.with_overrides(w, grid_h=gh, grid_w=gw)
+    if args.cache_frames:
+        w = wl.with_overrides(w, cache_frames=args.cache_frames)
     g = B.Geom(w.heads, w.head_dim, w.grid_h, w.grid_w, w.tile_h, w.tile_w, w.q_frames, w.cache_frames,
                radius, radius, topk, dtype=B.LCSA_BF16, tile_t=tile_t)
     n_qb = g.n_qb
@@ -171,7 +178,11 @@ def main() -> int:
         kvalid = np.where(idx >= 0, valid_tok[np.maximum(idx, 0) % g.nb], 0).sum(axis=-1)   # [h][qb]
         qvalid = valid_tok[np.arange(n_qb) % g.nb][None, :]
         useful.append(4.0 * g.head_dim * float((qvalid * kvalid).sum()))
-        issued.append(4.0 * 128 * 128 * g.head_dim * float(cnt.sum()))
+        # the kernel computes whole 32-query x 32-key matrix-core tiles: valid counts rounded up to 32
+        up32 = -(-valid_tok // 32) * 32
+        kiss = np.where(idx >= 0, up32[np.maximum(idx, 0) % g.nb], 0).sum(axis=-1)
+        qiss = up32[np.arange(n_qb) % g.nb][None, :]
+        issued.append(4.0 * g.head_dim * float((qiss * kiss).sum()))
     useful_flop, issued_flop = float(np.mean(useful)), float(np.mean(issued))
     attn_avg_ms = float(attn_ms.mean())
     achieved = useful_flop / (attn_avg_ms * 1e-3) / 1e12
@@ -198,7 +209,7 @@ def main() -> int:
         "config": {"workload": WORKLOAD_TEXT[args.workload], "heads": g.heads, "head_dim": g.head_dim,
                    "layers_per_step": n_layers, "q_tokens": tok_new, "kv_tokens": w.cache_frames * w.tokens_per_frame,
                    "block_shape": [tile_t, w.tile_h, w.tile_w], "blocks_per_group": g.nb, "query_blocks": n_qb,
-                   "topk": topk, "radius": radius},
+                   "grid": [w.grid_h, w.grid_w], "cache_frames": w.cache_frames, "topk": topk, "radius": radius},
         "effective_tflops_whole_path": round(useful_flop / (ms_per_layer * 1e-3) / 1e12, 2),
         "kernel_ms_per_layer": {"kv_cache_append": round(float(brk[0]), 5), "pool_blocks": round(float(brk[1]), 5),
                                 "select_blocks": round(float(brk[2]), 5), "sparse_attn_fwd": round(attn_avg_ms, 5)},
@@ -206,7 +217,7 @@ def main() -> int:
                     "pool_blocks": round(pool_bytes / (brk[1] * 1e-3) / 1e9, 1)},
         "roofline": {"kernel": "attn_mfma_kernel", "bound": "mfma", "achieved": round(achieved, 2),
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
-                     "traffic": ATTN_TRAFFIC_BYTES.get((args.workload, topk)) if not args.blocks and args.radius is None else None,
+                     "traffic": ATTN_TRAFFIC_BYTES.get((args.workload, topk)) if not (args.blocks or args.grid or args.cache_frames) and args.radius is None else None,
                      "flop_per_launch_useful": useful_flop, "flop_per_launch_issued": issued_flop,
                      "issued_tflops": round(issued_flop / (attn_avg_ms * 1e-3) / 1e12, 2),
                      "avg_launch_ms": round(attn_avg_ms, 5), "min_launch_ms": round(float(attn_ms.min()), 5)},

@@ -146,7 +146,7 @@ int32_t lcsa_select_blocks(const lcsa_geom *geom, const float *pooled_q, const l
  * frames, each with its own strides.  lse: device float [token][head] or NULL, natural
  * log of the softmax denominator.  scale <= 0 selects 1/sqrt(head_dim).  Products are
  * formed from the stored element type with float accumulation and a float online
- * softmax; bf16 probabilities feed the second product on the matrix-core path.
+ * softmax; on the matrix-core path probabilities and V enter the second product as IEEE half.
  * Rows with sel_cnt = 0 produce zeros (lse = -inf).
  */
 int32_t lcsa_sparse_attn_fwd(const lcsa_geom *geom,

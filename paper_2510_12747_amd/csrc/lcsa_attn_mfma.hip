@@ -5,15 +5,19 @@
 // query blocks of the same spatial tile, which share their window), its own K and V tile
 // buffers in LDS, and wavefront w of a group owns query rows 32w .. 32w+31.
 //
-// Per selected key block a group runs three stages
+// Per selected key block a group runs
 //     QK   S^T = K Q^T        v_mfma_f32_32x32x16_bf16  (keys on the row axis, queries on lanes)
 //     SM   online softmax     VALU, fp32 (eq. 1; scale folded into exp2; lazily updated reference)
 //     PV   O^T += V^T P^T     v_mfma_f32_32x32x16_f16   (channels on the row axis, queries on lanes)
-// and the two groups run one stage apart, every stage ending in a workgroup barrier: each
-// SIMD holds one wavefront of either group, so while one issues matrix instructions the
-// other mostly issues vector instructions.  Left to themselves two independent wavefronts
-// fall into step (both want the matrix pipe, then both want the vector pipe); the fixed
-// stagger keeps the two pipes busy together.
+// as four phases (two matrix, two vector), every phase ending in a workgroup barrier, and the
+// two groups run two phases apart: each SIMD holds one wavefront of either group, so while one
+// issues matrix instructions the other issues vector instructions.  Left to themselves two
+// independent wavefronts fall into step (both want the matrix pipe, then both want the vector
+// pipe); the fixed stagger keeps the two pipes busy together.
+//
+// A block clipped by the grid border holds its valid tokens first: only the 32-key groups (and
+// 32-query wavefronts) that contain valid tokens are computed, and at most one 16-key fragment
+// per block needs a mask.
 //
 // Transposed products put every query column in one lane (and its partner lane^32): the
 // softmax statistics need one cross-lane exchange per block, the rescale factor of O is a
@@ -42,7 +46,7 @@ typedef __attribute__((ext_vector_type(2))) _Float16 f16x2;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 
 constexpr int kTileBytes = 128 * 256;
-constexpr int kAhead = 4;            // operand fragments in flight ahead of the matrix instruction using them
+constexpr int kAhead = 3;            // operand fragments in flight ahead of the matrix instruction using them
 constexpr int kRing = kAhead + 1;
 constexpr int kSplit = 4;            // softmax fragments (of 8) done in the first vector phase; the rest in the second
 constexpr float kLog2e = 1.4426950408889634f;
@@ -90,26 +94,28 @@ __device__ inline void softmax_fragment(const f32x16 &sc, int first, float scale
     }
 }
 
-// Largest score of each query column over the block's 128 keys (both lanes of a query agree).
-__device__ inline float block_row_max(const f32x16 (&sc)[4]) {
-    float mx = sc[0][0];
+// Largest score of each query column over the block's first nf 16-key fragments (both lanes of a
+// query agree); nf is wavefront-uniform.
+__device__ inline float block_row_max(const f32x16 (&sc)[4], int nf) {
+    float mx = -__builtin_inff();
 #pragma unroll
-    for (int kg = 0; kg < 4; ++kg)
+    for (int ks = 0; ks < 8; ++ks)
+        if (ks < nf) {
 #pragma unroll
-        for (int i = 0; i < 16; ++i) mx = fmaxf(mx, sc[kg][i]);
+            for (int j = 0; j < 8; ++j) mx = fmaxf(mx, sc[ks >> 1][(ks & 1) * 8 + j]);
+        }
     return fmaxf(mx, __shfl_xor(mx, 32));
 }
 
-// A selected key block as the loop wants it: ring-slot tile index and which axes are clipped.
-//   bits 0..23 tile index (slot*nb + tile), bit 30 clipped in h, bit 31 clipped in w
+// A selected key block as the loop wants it: ring-slot tile index and its number of valid keys.
+//   bits 0..23 tile index (slot*nb + tile), bits 24..30 valid keys - 1
 __device__ inline uint32_t pack_block(const KGeom &g, const KCache &c, int kb, int ph, int pw) {
     const int f = kb / g.nb, kt = kb - f * g.nb;
     const int kby = kt / g.tx, kbx = kt - kby * g.tx;
-    uint32_t v = (uint32_t)(slot_of_frame(c.start, g.cap, f) * g.nb + kt);
-    if (kby == g.ty - 1 && ph < g.th) v |= 1u << 30;
-    if (kbx == g.tx - 1 && pw < g.tw) v |= 1u << 31;
-    return v;
+    const int vh = kby == g.ty - 1 ? ph : g.th, vw = kbx == g.tx - 1 ? pw : g.tw;
+    return (uint32_t)(slot_of_frame(c.start, g.cap, f) * g.nb + kt) | (uint32_t)(g.tt * vh * vw - 1) << 24;
 }
+__device__ inline int block_keys(uint32_t blk) { return (int)(blk >> 24) + 1; }
 
 __global__ __launch_bounds__(512, 2) void attn_mfma_kernel(
     KGeom g, KCache c, const __bf16 *__restrict__ q, int64_t q_st, int64_t q_sh,
@@ -156,26 +162,22 @@ __global__ __launch_bounds__(512, 2) void attn_mfma_kernel(
     const int qvh = min(g.th, g.H - by * g.th), qvw = min(g.tw, g.W - bx * g.tw);
     const int ph = g.H - (g.ty - 1) * g.th, pw = g.W - (g.tx - 1) * g.tw;   // extent of clipped edge tiles
 
-    // ---- the first K tile is requested before anything else so that its latency overlaps the set-up
+    // ---- the first K tile is requested before anything else so that its latency overlaps the set-up.
+    // Wavefront w copies rows 32w..32w+31 of a K tile, which are only read if they hold valid keys.
     const char *k_head = (const char *)c.k + (int64_t)head * g.cap * g.nb * kTileBytes;
     const char *v_head = (const char *)c.v + (int64_t)head * g.cap * g.nb * kTileBytes;
     auto tile_off = [](uint32_t blk) { return (int64_t)(blk & 0xffffffu) * kTileBytes; };
+    auto key_groups = [](uint32_t blk) { return (block_keys(blk) + 31) >> 5; };
     const uint32_t copy_voff = wave * 8192 + lane * 16;     // this lane's byte offset inside any tile image
+    const uint32_t kdst = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)((LCSA_LDS unsigned char *)k_lds) + wave * 8192);
+    const uint32_t vdst = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)((LCSA_LDS unsigned char *)v_lds) + wave * 8192);
+    uint32_t blk = 0;
     if (cnt > 0) {
-        const uint32_t blk0 = __builtin_amdgcn_readfirstlane(pack_block(g, c, sel[0], ph, pw));
-        const uint32_t kdst0 = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)((LCSA_LDS unsigned char *)k_lds) + wave * 8192);
+        blk = __builtin_amdgcn_readfirstlane(pack_block(g, c, sel[0], ph, pw));
+        if (wave < key_groups(blk)) {
 #pragma unroll
-        for (int piece = 0; piece < 8; ++piece) copy_piece_to_lds(k_head + tile_off(blk0), copy_voff, kdst0, piece);
-    }
-
-    // tile-token coordinates of keys `lane` and `lane + 64`, for the validity ballots of clipped tiles
-    // (four small numbers packed into one register; they are only unpacked for clipped tiles)
-    uint32_t key_rc;
-    {
-        int ft, kr0, kc0, kr1, kc1;
-        block_token(g, lane, g.th, g.tw, ft, kr0, kc0);
-        block_token(g, lane + 64, g.th, g.tw, ft, kr1, kc1);
-        key_rc = (uint32_t)kr0 | ((uint32_t)kc0 << 8) | ((uint32_t)kr1 << 16) | ((uint32_t)kc1 << 24);
+            for (int piece = 0; piece < 8; ++piece) copy_piece_to_lds(k_head + tile_off(blk), copy_voff, kdst, piece);
+        }
     }
 
     // ---- Q fragments (B operand of S^T = K Q^T): lane holds query ql of this wavefront, channels 16s+8*half..+8
@@ -184,6 +186,8 @@ __global__ __launch_bounds__(512, 2) void attn_mfma_kernel(
     const bool q_valid = block_token(g, tq, qvh, qvw, qft, qr, qc) && active;
     const int64_t token = q_valid ? raster_token(g, fq, qft, by * g.th + qr, bx * g.tw + qc)
                                   : raster_token(g, fq, 0, by * g.th, bx * g.tw);       // clamp padding rows
+    // a wavefront whose 32 query rows are all padding only takes part in the copies and barriers
+    const bool wave_on = active && wave * 32 < g.tt * qvh * qvw;
     bf16x8 bq[8];
     {
         const __bf16 *qp = q + token * q_st + (int64_t)head * q_sh + half * 8;
@@ -211,7 +215,6 @@ __global__ __launch_bounds__(512, 2) void attn_mfma_kernel(
         for (int i = 0; i < 16; ++i) oacc[dt][i] = 0.f;
     float m_run = -__builtin_inff(), l_run = 0.f;
 
-    uint32_t blk = __builtin_amdgcn_readlane(blk_chunk, 0);
     __builtin_amdgcn_s_waitcnt(0x0F70);    // vmcnt(0), visible to the compiler: Q fragments, ids and the first K tile have arrived
     stage_barrier();                       // first K tiles of both groups are in LDS
     if (grp8 == 1) { stage_barrier(); stage_barrier(); }   // group 1 runs two phases behind group 0
@@ -220,6 +223,31 @@ __global__ __launch_bounds__(512, 2) void attn_mfma_kernel(
     uint32_t blk_next = 0;
     bool has_next = false;
     float l_before = 0.f;
+    int ng = 4, ng_prev = 4;               // 32-key groups of the current / previous block that hold valid keys
+
+    // O^T += V^T P^T over the first `groups` 32-key groups (2 k-steps each) x 4 channel groups.
+    // Operand fragments are read kAhead matrix instructions ahead through a register ring; a group
+    // without valid keys ends the product (its operands, already requested, are dropped).
+    auto pv_phase = [&](int groups) {
+        f16x8 va[kRing];
+#pragma unroll
+        for (int n = 0; n < kAhead; ++n) va[n % kRing] = *(const f16x8 *)(v_lds + (n & 3) * 8192 + v_off(n >> 2));
+        __builtin_amdgcn_sched_group_barrier(0x100, kAhead, 0);
+#pragma unroll
+        for (int kg = 0; kg < 4; ++kg)
+            if (kg < groups) {
+#pragma unroll
+                for (int n = 8 * kg; n < 8 * kg + 8; ++n) {
+                    const int ks = n >> 2, dt = n & 3;
+                    if (n + kAhead < 32) {
+                        va[(n + kAhead) % kRing] = *(const f16x8 *)(v_lds + ((n + kAhead) & 3) * 8192 + v_off((n + kAhead) >> 2));
+                        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                    }
+                    oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(va[n % kRing], pfrag[ks], oacc[dt], 0, 0, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                }
+            }
+    };
 
     // Four phases per block, each ending in a workgroup barrier:
     //   P1  PV(i-1)            matrix     P3  softmax(i), first fragments   vector
@@ -234,26 +262,39 @@ __global__ __launch_bounds__(512, 2) void attn_mfma_kernel(
         const bool on = it < cnt;
         f32x16 sacc[4];                    // S^T of this block: produced in P2, consumed in P3 and P4
 
-        // ================= P1: O^T += V^T P^T of the previous block (8 k-steps x 4 channel groups) ====
-        if (pv_on) {
-            __builtin_amdgcn_s_setprio(2);
-            f16x8 va[kRing];
+        // S^T = K Q^T over the first `groups` key groups x 8 k-steps; the 8 copy instructions of V(i) go along
+        auto qk_phase = [&](int groups, const char *vsrc) {
+            bf16x8 ka[kRing];
 #pragma unroll
-            for (int n = 0; n < kAhead; ++n) va[n % kRing] = *(const f16x8 *)(v_lds + (n & 3) * 8192 + v_off(n >> 2));
-#pragma unroll
-            for (int n = 0; n < 32; ++n) {
-                const int ks = n >> 2, dt = n & 3;
-                if (n + kAhead < 32)
-                    va[(n + kAhead) % kRing] = *(const f16x8 *)(v_lds + ((n + kAhead) & 3) * 8192 + v_off((n + kAhead) >> 2));
-                oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(va[n % kRing], pfrag[ks], oacc[dt], 0, 0, 0);
-            }
+            for (int n = 0; n < kAhead; ++n) ka[n % kRing] = *(const bf16x8 *)(k_lds + (n >> 3) * 8192 + k_off(n & 7));
             __builtin_amdgcn_sched_group_barrier(0x100, kAhead, 0);
 #pragma unroll
-            for (int i = 0; i < 32 - kAhead; ++i) {
-                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            for (int kg = 0; kg < 4; ++kg) {
+                if (kg < groups) {
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) sacc[kg][i] = 0.f;
+#pragma unroll
+                    for (int n = 8 * kg; n < 8 * kg + 8; ++n) {
+                        const int s = n & 7;
+                        if ((n & 3) == 0) copy_piece_to_lds(vsrc, copy_voff, vdst, n >> 2);     // one copy instruction per 4 MFMAs
+                        if (n + kAhead < 32) {
+                            ka[(n + kAhead) % kRing] = *(const bf16x8 *)(k_lds + ((n + kAhead) >> 3) * 8192 + k_off((n + kAhead) & 7));
+                            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                        }
+                        sacc[kg] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[n % kRing], bq[s], sacc[kg], 0, 0, 0);
+                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    }
+                } else {
+                    copy_piece_to_lds(vsrc, copy_voff, vdst, 2 * kg);
+                    copy_piece_to_lds(vsrc, copy_voff, vdst, 2 * kg + 1);
+                }
             }
-            __builtin_amdgcn_sched_group_barrier(0x008, kAhead, 0);
+        };
+
+        // ================= P1: O^T += V^T P^T of the previous block ===================================
+        if (pv_on && wave_on) {
+            __builtin_amdgcn_s_setprio(2);
+            pv_phase(ng_prev);
             __builtin_amdgcn_s_setprio(0);
         }
         if (on) wait_vm0();                // K(i) (this wavefront's part) has landed
@@ -261,32 +302,19 @@ __global__ __launch_bounds__(512, 2) void attn_mfma_kernel(
         stage_barrier();
         __builtin_amdgcn_sched_barrier(0);
 
-        // ================= P2: S^T = K Q^T (4 key groups x 8 k-steps); V(i) copy issued alongside =====
+        // ================= P2: S^T = K Q^T; V(i) copy issued alongside ================================
         if (on) {
             blk = it == 0 ? blk : blk_next;
-            __builtin_amdgcn_s_setprio(2);
+            ng = key_groups(blk);
             const char *vsrc = v_head + tile_off(blk);
-            const uint32_t vdst = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)((LCSA_LDS unsigned char *)v_lds) + wave * 8192);
-            bf16x8 ka[kRing];
+            if (wave_on) {
+                __builtin_amdgcn_s_setprio(2);
+                qk_phase(ng, vsrc);
+                __builtin_amdgcn_s_setprio(0);
+            } else {
 #pragma unroll
-            for (int n = 0; n < kAhead; ++n) ka[n % kRing] = *(const bf16x8 *)(k_lds + (n >> 3) * 8192 + k_off(n & 7));
-            __builtin_amdgcn_sched_group_barrier(0x100, kAhead, 0);
-#pragma unroll
-            for (int n = 0; n < 32; ++n) {
-                const int kg = n >> 3, s = n & 7;
-                if (s == 0) {
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) sacc[kg][i] = 0.f;
-                }
-                if ((n & 3) == 0) copy_piece_to_lds(vsrc, copy_voff, vdst, n >> 2);     // one of the 8 copy instructions per 4 MFMAs
-                if (n + kAhead < 32) {
-                    ka[(n + kAhead) % kRing] = *(const bf16x8 *)(k_lds + ((n + kAhead) >> 3) * 8192 + k_off((n + kAhead) & 7));
-                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-                }
-                sacc[kg] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[n % kRing], bq[s], sacc[kg], 0, 0, 0);
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                for (int piece = 0; piece < 8; ++piece) copy_piece_to_lds(vsrc, copy_voff, vdst, piece);
             }
-            __builtin_amdgcn_s_setprio(0);
             // next block; every 64 iterations the per-lane chunk is refilled (the read of the fresh
             // value sits inside the branch so that the wait for that load does too)
             has_next = it + 1 < cnt;
@@ -305,40 +333,39 @@ __global__ __launch_bounds__(512, 2) void attn_mfma_kernel(
 
         // ================= P3: online softmax, first half; K(i+1) copy issued alongside ===============
         const char *ksrc = k_head + tile_off(blk_next);
-        const uint32_t kdst = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)((LCSA_LDS unsigned char *)k_lds) + wave * 8192);
-        if (on) {
-            // everyone in the group is done reading K: the next K tile may overwrite it
-            if (has_next) { copy_piece_to_lds(ksrc, copy_voff, kdst, 0); copy_piece_to_lds(ksrc, copy_voff, kdst, 1); }
-
-            // padding keys of clipped tiles get weight exactly zero
-            if (blk >> 30) {
-                const int kvh = (blk & (1u << 30)) ? ph : g.th, kvw = (blk & (1u << 31)) ? pw : g.tw;
-                const int kr0 = key_rc & 255, kc0 = (key_rc >> 8) & 255, kr1 = (key_rc >> 16) & 255, kc1 = key_rc >> 24;
-                const uint64_t b0 = __ballot(kr0 < kvh && kc0 < kvw);   // keys 0..63
-                const uint64_t b1 = __ballot(kr1 < kvh && kc1 < kvw);   // keys 64..127
-                const uint32_t key_ok[4] = {(uint32_t)b0, (uint32_t)(b0 >> 32), (uint32_t)b1, (uint32_t)(b1 >> 32)};
+        const bool k_copy = on && has_next && wave < key_groups(blk_next);    // this wavefront's rows of K(i+1) hold keys
+        const int nv = block_keys(blk);
+        const int nf = (nv + 15) >> 4;     // 16-key fragments that hold valid keys
+        // everyone in the group is done reading K: the next K tile may overwrite it
+        if (k_copy) { copy_piece_to_lds(ksrc, copy_voff, kdst, 0); copy_piece_to_lds(ksrc, copy_voff, kdst, 1); }
+        if (on && wave_on) {
+            // Padding keys get weight exactly zero.  Valid keys come first in a block, so only the last
+            // fragment can be mixed: accumulator register j of fragment ks is key 16*ks + 8*half + j.
+            if (nv & 15) {
+                const int thr = (nv & 15) - half * 8;      // registers j >= thr of the last fragment are padding
 #pragma unroll
-                for (int kg = 0; kg < 4; ++kg) {
-                    // accumulator register i of key group kg is key kg*32 + (i>>3)*16 + half*8 + (i&7)
-                    const uint32_t mbits = key_ok[kg] >> (half * 8);
+                for (int ks = 0; ks < 8; ++ks)
+                    if (ks == nf - 1) {
 #pragma unroll
-                    for (int i = 0; i < 16; ++i)
-                        if (!((mbits >> ((i >> 3) * 16 + (i & 7))) & 1u)) sacc[kg][i] = -__builtin_inff();
-                }
+                        for (int j = 0; j < 8; ++j)
+                            if (j >= thr) sacc[ks >> 1][(ks & 1) * 8 + j] = -__builtin_inff();
+                    }
             }
-
             // Reference point of the exponentials.  Any per-query reference gives the same softmax after
             // the final normalisation; it only has to keep 2^(score - reference) inside half's range.
             // The first block sets it to its exact row maximum; later blocks reuse it without looking
             // for their maximum (which would cost a pass over all scores) and are checked afterwards:
             // see the end of P4.
-            if (it == 0) m_run = block_row_max(sacc) * scale_log2;
-            if (has_next) { copy_piece_to_lds(ksrc, copy_voff, kdst, 2); copy_piece_to_lds(ksrc, copy_voff, kdst, 3); }
+            if (it == 0) m_run = block_row_max(sacc, nf) * scale_log2;
+        }
+        if (k_copy) { copy_piece_to_lds(ksrc, copy_voff, kdst, 2); copy_piece_to_lds(ksrc, copy_voff, kdst, 3); }
+        if (on && wave_on) {
             l_before = l_run;
             // probabilities -> half for the matrix product; row sum in float
 #pragma unroll
             for (int ks = 0; ks < kSplit; ++ks) {
-                softmax_fragment(sacc[ks >> 1], (ks & 1) * 8, scale_log2, m_run, l_run, pfrag[ks]);
+                if (ks < nf) softmax_fragment(sacc[ks >> 1], (ks & 1) * 8, scale_log2, m_run, l_run, pfrag[ks]);
+                else pfrag[ks] = f16x8{0, 0, 0, 0, 0, 0, 0, 0};
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
@@ -347,19 +374,22 @@ __global__ __launch_bounds__(512, 2) void attn_mfma_kernel(
         __builtin_amdgcn_sched_barrier(0);
 
         // ================= P4: online softmax, second half =============================================
-        if (on) {
-            if (has_next) { copy_piece_to_lds(ksrc, copy_voff, kdst, 4); copy_piece_to_lds(ksrc, copy_voff, kdst, 5); }
+        if (k_copy) { copy_piece_to_lds(ksrc, copy_voff, kdst, 4); copy_piece_to_lds(ksrc, copy_voff, kdst, 5); }
+        if (on && wave_on) {
 #pragma unroll
             for (int ks = kSplit; ks < 8; ++ks) {
-                if (has_next && ks == 5) { copy_piece_to_lds(ksrc, copy_voff, kdst, 6); copy_piece_to_lds(ksrc, copy_voff, kdst, 7); }
-                softmax_fragment(sacc[ks >> 1], (ks & 1) * 8, scale_log2, m_run, l_run, pfrag[ks]);
+                if (ks < nf) softmax_fragment(sacc[ks >> 1], (ks & 1) * 8, scale_log2, m_run, l_run, pfrag[ks]);
+                else pfrag[ks] = f16x8{0, 0, 0, 0, 0, 0, 0, 0};
                 __builtin_amdgcn_sched_barrier(0);
             }
-            // Check of the reference: this lane's 64 probabilities sum to less than 2^14, hence none of them
-            // left half's range.  Otherwise (a block whose scores tower over everything seen before, or
+        }
+        if (k_copy) { copy_piece_to_lds(ksrc, copy_voff, kdst, 6); copy_piece_to_lds(ksrc, copy_voff, kdst, 7); }
+        if (on && wave_on) {
+            // Check of the reference: this lane's probabilities of the block sum to less than 2^14, hence none
+            // of them left half's range.  Otherwise (a block whose scores tower over everything seen before, or
             // non-finite input) redo the block against its exact maximum, rescaling the running sums.
             if (__ballot(!(l_run - l_before < 16384.f))) {
-                const float m_new = fmaxf(m_run, block_row_max(sacc) * scale_log2);
+                const float m_new = fmaxf(m_run, block_row_max(sacc, nf) * scale_log2);
                 const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
                 l_run = l_before * alpha;
 #pragma unroll
@@ -369,10 +399,13 @@ __global__ __launch_bounds__(512, 2) void attn_mfma_kernel(
                 m_run = m_new;
 #pragma unroll
                 for (int ks = 0; ks < 8; ++ks)
-                    softmax_fragment(sacc[ks >> 1], (ks & 1) * 8, scale_log2, m_run, l_run, pfrag[ks]);
+                    if (ks < nf) softmax_fragment(sacc[ks >> 1], (ks & 1) * 8, scale_log2, m_run, l_run, pfrag[ks]);
             }
-            // V(i) has landed (the 8 newer copies in flight are the next K tile, if any)
-            if (has_next) wait_vm8(); else wait_vm0();
+        }
+        if (on) {
+            // V(i) has landed (the 8 newer copies in flight are this wavefront's part of the next K tile, if any)
+            if (k_copy) wait_vm8(); else wait_vm0();
+            ng_prev = ng;
         }
         __builtin_amdgcn_sched_barrier(0);
         stage_barrier();

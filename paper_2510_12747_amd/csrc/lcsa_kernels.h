@@ -22,7 +22,8 @@ struct KGeom {
 //   K tiles : [heads][cap][nb][tile image]   element type = geometry dtype; cap ring slots, one per group
 //   V tiles : same extent
 //   pooled  : float [heads][cap*nb][d], indexed by ring slot
-// Tokens of a block are ordered (frame in group, tile row, tile col).
+// Tokens of a block are ordered (frame in group, tile row, tile col) over the block's valid extent:
+// a clipped block holds its valid tokens first and padding after them.
 // Tile image, generic layout: K and V row-major [bt][d], padded tokens zero.
 // Tile image, matrix-core layout (bf16, d = 128, bt = 128): 128 rows of 256 bytes,
 //   the 16-byte chunk j of row r stored at chunk position j ^ (r & 15);
@@ -41,14 +42,16 @@ __host__ __device__ inline int slot_of_frame(int start, int cap, int f) {
     return s >= cap ? s - cap : s;
 }
 
-// Block token i -> (frame within the group, row, col inside the tile); true if it exists in a tile
-// clipped to vh x vw.
+// Block token i -> (frame within the group, row, col inside the tile) of a tile clipped to vh x vw.
+// The valid tokens of a block come first, in (frame, row, col) order over the clipped extent;
+// positions tt*vh*vw .. bt-1 are padding (false is returned for them).
 __host__ __device__ inline bool block_token(const KGeom &g, int i, int vh, int vw, int &ft, int &r, int &c) {
-    ft = i / g.ts;
-    const int rem = i - ft * g.ts;
-    r = rem / g.tw;
-    c = rem - r * g.tw;
-    return i < g.bt && r < vh && c < vw;
+    const int per_frame = vh * vw;
+    ft = i / per_frame;
+    const int rem = i - ft * per_frame;
+    r = rem / vw;
+    c = rem - r * vw;
+    return i < g.tt * per_frame;
 }
 // Raster token index of (group, frame in group, absolute row, absolute col).
 __host__ __device__ inline int64_t raster_token(const KGeom &g, int group, int ft, int row, int col) {

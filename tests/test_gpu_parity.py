@@ -300,6 +300,27 @@ def test_paper_block_shape_2x8x8_paper_scale_sampled_rows():
     run_primed(w, rows=sample_rows(og, 40), tile_t=2)
 
 
+@pytest.mark.parametrize("window_mode", [0, 1])
+def test_paper_block_shape_high_res_72x72_window(window_mode):
+    """96x168 latent grid (a 1536x2688 video), (2,8,8) blocks, a window of 9x9 tiles = 72x72 tokens
+    (Sec. 3.3; appendix figure on locality-constrained attention), both boundary rules of Fig. 3."""
+    w = wl.with_overrides(wl.WORKLOADS["ultra"], name="hires-2x8x8", grid_h=96, grid_w=168, tile_h=8, tile_w=8,
+                          radius=32)
+    g, og = geoms(w, tile_t=2, window_mode=window_mode)
+    assert g.nb == 252 and oracle.allowed(0, 4 * 21 + 4, og) and not oracle.allowed(136, 136 + 5, og)
+    run_primed(w, rows=sample_rows(og, 40), tile_t=2, window_mode=window_mode)
+
+
+@pytest.mark.parametrize("tile_t,tile_h,tile_w", [(1, 8, 16), (2, 8, 8)])
+def test_clipped_blocks_with_odd_valid_counts(tile_t, tile_h, tile_w):
+    """21x37 grid: edge blocks hold 25/40/80 (8x16 tiles) or 50/80 ((2,8,8) blocks) valid tokens, so the
+    matrix-core kernel meets partly filled 32-key groups and 16-key fragments, on keys and on queries."""
+    w = wl.with_overrides(wl.WORKLOADS["small"], name=f"odd-{tile_t}x{tile_h}x{tile_w}", heads=2, grid_h=21, grid_w=37,
+                          tile_h=tile_h, tile_w=tile_w, radius=-1, topk=12)
+    run_primed(w, tile_t=tile_t, check_lse=True)
+    run_primed(w, tile_t=tile_t, radius=12, topk=5)
+
+
 def test_temporal_blocks_generic_f32():
     w = wl.with_overrides(wl.WORKLOADS["tiny"], name="tiny-2x4x4", heads=2, grid_h=10, grid_w=14, radius=4, topk=3)
     say("f32 generic path, (2,4,4) blocks on a 10x14 grid")
