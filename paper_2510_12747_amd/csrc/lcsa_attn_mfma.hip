@@ -149,38 +149,19 @@ __global__ __launch_bounds__(512, 2) void attn_mfma_kernel(
     const int item = 2 * pair + grp8, other = 2 * pair + (grp8 ^ 1);
     const bool active = item < total_items;
     int head = 0, qb = 0, cnt = 0, other_cnt = 0;
-    if (active) { item_row(item, head, qb); cnt = sel_cnt[(int64_t)head * n_qb + qb]; }
+    int32_t first_ids = -1;                // selected block `lane` of this row, requested together with the count
+    if (active) {
+        item_row(item, head, qb);
+        cnt = sel_cnt[(int64_t)head * n_qb + qb];
+        if (lane < g.topk) first_ids = sel_idx[((int64_t)head * n_qb + qb) * g.topk + lane];
+    }
     if (other < total_items) { int h2, q2; item_row(other, h2, q2); other_cnt = sel_cnt[(int64_t)h2 * n_qb + q2]; }
-    cnt = __builtin_amdgcn_readfirstlane(cnt);
-    other_cnt = __builtin_amdgcn_readfirstlane(other_cnt);
-    const int n_iter = max(cnt, other_cnt);
-    const int64_t row = (int64_t)head * n_qb + qb;
-    const int32_t *sel = sel_idx + row * g.topk;
-
     const int fq = qb / g.nb, tile = qb - fq * g.nb;
     const int by = tile / g.tx, bx = tile - by * g.tx;
     const int qvh = min(g.th, g.H - by * g.th), qvw = min(g.tw, g.W - bx * g.tw);
-    const int ph = g.H - (g.ty - 1) * g.th, pw = g.W - (g.tx - 1) * g.tw;   // extent of clipped edge tiles
 
-    // ---- the first K tile is requested before anything else so that its latency overlaps the set-up.
-    // Wavefront w copies rows 32w..32w+31 of a K tile, which are only read if they hold valid keys.
-    const char *k_head = (const char *)c.k + (int64_t)head * g.cap * g.nb * kTileBytes;
-    const char *v_head = (const char *)c.v + (int64_t)head * g.cap * g.nb * kTileBytes;
-    auto tile_off = [](uint32_t blk) { return (int64_t)(blk & 0xffffffu) * kTileBytes; };
-    auto key_groups = [](uint32_t blk) { return (block_keys(blk) + 31) >> 5; };
-    const uint32_t copy_voff = wave * 8192 + lane * 16;     // this lane's byte offset inside any tile image
-    const uint32_t kdst = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)((LCSA_LDS unsigned char *)k_lds) + wave * 8192);
-    const uint32_t vdst = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)((LCSA_LDS unsigned char *)v_lds) + wave * 8192);
-    uint32_t blk = 0;
-    if (cnt > 0) {
-        blk = __builtin_amdgcn_readfirstlane(pack_block(g, c, sel[0], ph, pw));
-        if (wave < key_groups(blk)) {
-#pragma unroll
-            for (int piece = 0; piece < 8; ++piece) copy_piece_to_lds(k_head + tile_off(blk), copy_voff, kdst, piece);
-        }
-    }
-
-    // ---- Q fragments (B operand of S^T = K Q^T): lane holds query ql of this wavefront, channels 16s+8*half..+8
+    // ---- Q fragments (B operand of S^T = K Q^T), requested before the counts are waited for:
+    // lane holds query ql of this wavefront, channels 16s+8*half..+8
     const int tq = wave * 32 + ql;
     int qft, qr, qc;
     const bool q_valid = block_token(g, tq, qvh, qvw, qft, qr, qc) && active;
@@ -195,8 +176,29 @@ __global__ __launch_bounds__(512, 2) void attn_mfma_kernel(
         for (int s = 0; s < 8; ++s) bq[s] = *(const bf16x8 *)(qp + s * 16);
     }
 
+    cnt = __builtin_amdgcn_readfirstlane(cnt);
+    other_cnt = __builtin_amdgcn_readfirstlane(other_cnt);
+    const int n_iter = max(cnt, other_cnt);
+    const int64_t row = (int64_t)head * n_qb + qb;
+    const int32_t *sel = sel_idx + row * g.topk;
+
+    // ---- the first K tile is requested as soon as its id is known so that its latency overlaps the set-up.
+    // Wavefront w copies rows 32w..32w+31 of a K tile, which are only read if they hold valid keys.
+    const char *k_head = (const char *)c.k + (int64_t)head * g.cap * g.nb * kTileBytes;
+    const char *v_head = (const char *)c.v + (int64_t)head * g.cap * g.nb * kTileBytes;
+    auto tile_off = [](uint32_t blk) { return (int64_t)(blk & 0xffffffu) * kTileBytes; };
+    auto key_groups = [](uint32_t blk) { return (block_keys(blk) + 31) >> 5; };
+    const uint32_t copy_voff = wave * 8192 + lane * 16;     // this lane's byte offset inside any tile image
+    const uint32_t kdst = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)((LCSA_LDS unsigned char *)k_lds) + wave * 8192);
+    const uint32_t vdst = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)((LCSA_LDS unsigned char *)v_lds) + wave * 8192);
     // selected blocks of this row, 64 at a time, one per lane, already turned into tile indices
-    uint32_t blk_chunk = lane < cnt ? pack_block(g, c, sel[lane], ph, pw) : 0u;
+    const int ph = g.H - (g.ty - 1) * g.th, pw = g.W - (g.tx - 1) * g.tw;   // extent of clipped edge tiles
+    uint32_t blk_chunk = lane < cnt ? pack_block(g, c, first_ids, ph, pw) : 0u;
+    uint32_t blk = __builtin_amdgcn_readfirstlane(blk_chunk);
+    if (cnt > 0 && wave < key_groups(blk)) {
+#pragma unroll
+        for (int piece = 0; piece < 8; ++piece) copy_piece_to_lds(k_head + tile_off(blk), copy_voff, kdst, piece);
+    }
 
     // ---- per-lane LDS offsets
     // K operand: MFMA row m = ql reads key row pi(ql) of each 32-key group (bits 2,3 swapped)
