@@ -166,6 +166,30 @@ def main() -> int:
     brk = np.array([[e[4].elapsed_time(e[0]), e[0].elapsed_time(e[1]), e[1].elapsed_time(e[2]), e[2].elapsed_time(e[3])]
                     for e in ev]).mean(axis=0)
 
+    # ---- what this chip sustains on trivial loops, quoted beside the nominal peaks (outside the timed region):
+    # back-to-back bf16 matrix instructions on registers, and a 1 GiB device-to-device copy
+    prop = torch.cuda.get_device_properties(0)
+    n_cu = prop.multi_processor_count
+    probe_out = torch.empty(n_cu * 2 * 512, dtype=torch.float32, device="cuda")
+    probe_iters = 4000
+    B.lcsa_probe_mfma_bf16(n_cu * 2, 200, probe_out)
+    pe = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    pe[0].record()
+    B.lcsa_probe_mfma_bf16(n_cu * 2, probe_iters, probe_out)
+    pe[1].record()
+    torch.cuda.synchronize()
+    probe_tflops = n_cu * 2 * 8 * probe_iters * 32 * 32768.0 / (pe[0].elapsed_time(pe[1]) * 1e-3) / 1e12
+    csrc = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
+    cdst = torch.empty_like(csrc)
+    cdst.copy_(csrc)
+    pe[0].record()
+    for _ in range(5):
+        cdst.copy_(csrc)
+    pe[1].record()
+    torch.cuda.synchronize()
+    copy_gbs = 5 * 2 * float(1 << 30) / (pe[0].elapsed_time(pe[1]) * 1e-3) / 1e9
+    del csrc, cdst, probe_out
+
     # ---- algorithmic work of one attention launch (from the selection actually made) ---------------
     ty, tx = -(-w.grid_h // w.tile_h), -(-w.grid_w // w.tile_w)
     vh = np.minimum(w.tile_h, w.grid_h - np.arange(ty) * w.tile_h)
@@ -192,6 +216,8 @@ def main() -> int:
     append_bytes = 2 * tok_new * g.heads * g.head_dim * 2 + 2 * n_qb * 128 * 128 * 2 * g.heads \
         + n_qb * g.heads * g.head_dim * 4
     pool_bytes = tok_new * g.heads * g.head_dim * 2 + n_qb * g.heads * g.head_dim * 4
+    # selection: pooled Q and the pooled K of every visible block once, ids + counts out
+    select_bytes = (n_qb + w.cache_frames // tile_t * g.nb) * g.heads * g.head_dim * 4 + g.heads * n_qb * (topk + 1) * 4
 
     out = {
         "metric": "sparse_attn_ms_per_chunk_per_layer",
@@ -214,7 +240,12 @@ def main() -> int:
         "kernel_ms_per_layer": {"kv_cache_append": round(float(brk[0]), 5), "pool_blocks": round(float(brk[1]), 5),
                                 "select_blocks": round(float(brk[2]), 5), "sparse_attn_fwd": round(attn_avg_ms, 5)},
         "hbm_gbs": {"kv_cache_append": round(append_bytes / (brk[0] * 1e-3) / 1e9, 1),
-                    "pool_blocks": round(pool_bytes / (brk[1] * 1e-3) / 1e9, 1)},
+                    "pool_blocks": round(pool_bytes / (brk[1] * 1e-3) / 1e9, 1),
+                    "select_blocks": round(select_bytes / (brk[2] * 1e-3) / 1e9, 1)},
+        "device": {"name": prop.name, "compute_units": n_cu,
+                   "nominal_peak_tflops": PEAK_BF16_TFLOPS, "nominal_hbm_gbs": 8000.0},
+        "measured_peaks": {"mfma_bf16_register_loop_tflops": round(probe_tflops, 1),
+                           "device_copy_gbs": round(copy_gbs, 1)},
         "roofline": {"kernel": "attn_mfma_kernel", "bound": "mfma", "achieved": round(achieved, 2),
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
                      "traffic": ATTN_TRAFFIC_BYTES.get((args.workload, topk)) if not (args.blocks or args.grid or args.cache_frames) and args.radius is None else None,

@@ -156,6 +156,17 @@ int32_t lcsa_sparse_attn_fwd(const lcsa_geom *geom,
                              void *o, int64_t o_stride_tok, int64_t o_stride_head,
                              float *lse, float scale, void *stream);
 
+/* ---- measurement aid (not part of the method) ---------------------------------------------------- */
+
+/*
+ * Runs n_blocks workgroups of 8 wavefronts, every wavefront issuing 32*iters back-to-back
+ * v_mfma_f32_32x32x16_bf16 (32768 flop each) on operands that stay in registers: the matrix rate
+ * this chip sustains when nothing else limits it, which a benchmark can quote beside the nominal
+ * peak.  out: device float [n_blocks*512], receives one checksum per thread.
+ * 1 <= n_blocks <= 65536, 1 <= iters <= 2^20, else LCSA_EINVAL.
+ */
+int32_t lcsa_probe_mfma_bf16(float *out, int32_t n_blocks, int32_t iters, void *stream);
+
 /* Static, human-readable text for a status code. */
 const char *lcsa_status_string(int32_t status);
 /* Text of the last HIP error seen by this thread's most recent LCSA_EHIP ("" if none). */

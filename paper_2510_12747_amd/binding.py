@@ -97,11 +97,13 @@ def lib():
         L.lcsa_pool_blocks.argtypes = [_gp, _vp, _i64, _i64, _i32, _vp, _vp]
         L.lcsa_select_blocks.argtypes = [_gp, _vp, _vp, _vp, _vp, _vp, _vp]
         L.lcsa_sparse_attn_fwd.argtypes = [_gp, _vp, _i64, _i64, _vp, _vp, _vp, _vp, _i64, _i64, _vp, _f32, _vp]
+        L.lcsa_probe_mfma_bf16.argtypes = [_vp, _i32, _i32, _vp]
         L.lcsa_status_string.restype = ctypes.c_char_p
         L.lcsa_status_string.argtypes = [_i32]
         L.lcsa_last_hip_error.restype = ctypes.c_char_p
         for f in ("lcsa_cache_init", "lcsa_cache_reset", "lcsa_cache_valid_frames", "lcsa_cache_frame_slot",
-                  "lcsa_kv_cache_append", "lcsa_pool_blocks", "lcsa_select_blocks", "lcsa_sparse_attn_fwd"):
+                  "lcsa_kv_cache_append", "lcsa_pool_blocks", "lcsa_select_blocks", "lcsa_sparse_attn_fwd",
+                  "lcsa_probe_mfma_bf16"):
             getattr(L, f).restype = _i32
         _lib = L
     return _lib
@@ -127,6 +129,15 @@ def _tok(x: torch.Tensor):
     if not x.is_cuda or x.dim() != 3 or x.stride(2) != 1:
         raise LcsaError("expected a device tensor [tokens][heads][d] with contiguous d")
     return x.data_ptr(), x.stride(0), x.stride(1)
+
+
+def lcsa_probe_mfma_bf16(n_blocks: int, iters: int, out: torch.Tensor | None = None, stream=None) -> torch.Tensor:
+    """Measurement aid: n_blocks x 8 wavefronts x 32*iters back-to-back bf16 matrix instructions."""
+    if out is None:
+        out = torch.empty(n_blocks * 512, dtype=torch.float32, device="cuda")
+    assert out.is_contiguous() and out.dtype == torch.float32 and out.numel() >= n_blocks * 512
+    _check(lib().lcsa_probe_mfma_bf16(out.data_ptr(), n_blocks, iters, _stream(stream)), "lcsa_probe_mfma_bf16")
+    return out
 
 
 def lcsa_status_string(status: int) -> str:

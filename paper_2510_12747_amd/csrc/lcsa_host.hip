@@ -198,6 +198,11 @@ int32_t lcsa_sparse_attn_fwd(const lcsa_geom *geom, const void *q, int64_t q_str
     return hip_status(e);
 }
 
+int32_t lcsa_probe_mfma_bf16(float *out, int32_t n_blocks, int32_t iters, void *stream) {
+    if (!out || n_blocks < 1 || n_blocks > 65536 || iters < 1 || iters > (1 << 20)) return LCSA_EINVAL;
+    return hip_status(launch_probe_mfma(out, n_blocks, iters, (hipStream_t)stream));
+}
+
 const char *lcsa_status_string(int32_t status) {
     switch (status) {
     case LCSA_OK: return "ok";

@@ -81,6 +81,9 @@ hipError_t launch_attn_mfma(const KGeom &g, const KCache &c, const void *q, int6
                             void *o, int64_t o_st, int64_t o_sh, float *lse, float scale,
                             hipStream_t stream);
 
+// Measurement aid: n_blocks workgroups of 8 wavefronts, each wavefront issuing 32*iters matrix instructions.
+hipError_t launch_probe_mfma(float *out, int n_blocks, int iters, hipStream_t stream);
+
 // Largest number of admissible key blocks of any query block (host arithmetic).
 int max_candidates(const KGeom &g, int valid_groups);
 
