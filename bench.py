@@ -255,6 +255,40 @@ def main() -> int:
         "setup_s": round(setup_s, 1),
     }
 
+    # ---- streaming workloads: one video from an empty cache, chunk by chunk, for three top-k values -----
+    # (per-chunk time of the whole path while the ring fills and in the steady state; outside the timed region)
+    if w.n_chunks > 1:
+        s0 = wl.ChunkStream(w, 0)
+        vchunks = [tuple(dev(x) for x in s0.next()) for _ in range(w.n_chunks)]
+        fill = (w.cache_frames - w.q_frames) // w.q_frames           # chunks before the ring is full
+        streaming = {}
+        for rep, k in enumerate((topk, 16, 32, 64)):                  # the first pass only warms up
+            gk = B.Geom(w.heads, w.head_dim, w.grid_h, w.grid_w, w.tile_h, w.tile_w, w.q_frames, w.cache_frames,
+                        radius, radius, k, dtype=B.LCSA_BF16, tile_t=tile_t)
+            cache = B.lcsa_cache_init(gk)
+            pq = torch.empty(gk.heads, n_qb, gk.head_dim, dtype=torch.float32, device="cuda")
+            si = torch.empty(gk.heads, n_qb, k, dtype=torch.int32, device="cuda")
+            sc = torch.empty(gk.heads, n_qb, dtype=torch.int32, device="cuda")
+            oo = torch.empty_like(vchunks[0][0])
+            evs = [torch.cuda.Event(enable_timing=True) for _ in range(len(vchunks) + 1)]
+            torch.cuda.synchronize()
+            evs[0].record()
+            for i, (qd, kd, vd) in enumerate(vchunks):
+                B.lcsa_kv_cache_append(cache, kd, vd, w.q_frames)
+                B.lcsa_pool_blocks(gk, qd, w.q_frames, pq)
+                B.lcsa_select_blocks(gk, pq, cache, si, sc, want_gap=False)
+                B.lcsa_sparse_attn_fwd(gk, qd, cache, si, sc, oo)
+                evs[i + 1].record()
+            torch.cuda.synchronize()
+            ms = [evs[i].elapsed_time(evs[i + 1]) for i in range(len(vchunks))]
+            if rep:
+                streaming[f"topk_{k}"] = {"ring_filling_ms_per_chunk": [round(x, 4) for x in ms[:fill]],
+                                          "steady_ms_per_chunk_mean": round(float(np.mean(ms[fill:])), 4),
+                                          "steady_ms_per_chunk_min": round(float(np.min(ms[fill:])), 4)}
+            del cache, pq, si, sc, oo
+        out["streaming"] = {"chunks": len(vchunks), "chunks_before_ring_is_full": fill, **streaming}
+        del vchunks
+
     # ---- CPU oracle on the host cores: a bounded sample of the same workload ------------------------
     # Whole layer calls (pooling, scores, selection, attention of every row) of the first layers of
     # the workload, as many as fit in about 15 s (at least one, at most five); value = mean per layer.
