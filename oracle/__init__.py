@@ -8,7 +8,10 @@ code with the HIP library and never calls it.
 Paper passages followed: Sec. 3.2 "Stage 2" (blocks, pooling, coarse map,
 top-k, full attention on kept pairs), Sec. 3.3 / Fig. 3 (local window),
 eq. (1) (softmax with 1/sqrt(d)), appendix "Discussion on Stream VSR
-Pipelines" (sliding-window cache of recent latents + current chunk).
+Pipelines" (sliding-window cache of recent latents + current chunk),
+appendix on KV-cache eviction (importance-based eviction, head-wise and
+uniform; the paper prints no numbers for it that could pin these functions:
+their agreement with the authors' variant is unpinned).
 """
 from __future__ import annotations
 
@@ -212,6 +215,93 @@ class SlidingWindowCache:
     def visible(self):
         """(K, V) of every visible frame, oldest first: [valid_frames*H*W][heads][d]."""
         return np.concatenate(self.k_frames, 0), np.concatenate(self.v_frames, 0)
+
+
+def block_importance(S: np.ndarray, g: Geometry, kv_frames: int, scale: float = 0.0) -> np.ndarray:
+    """Importance of every visible key block, from the coarse block-to-block attention map of one chunk
+    (appendix on KV-cache eviction): the map is the softmax (eq. 1, scale 1/sqrt(d)) of the coarse scores
+    S (Sec. 3.2) over the key blocks a query block may attend to (Sec. 3.3); the importance of a key
+    block is the attention it receives summed over the chunk's query blocks.  [heads][n_kb], fp64."""
+    S = np.asarray(S, np.float64)
+    n_qb, n_kb = g.q_frames // g.tile_t * g.nb, kv_frames // g.tile_t * g.nb
+    assert S.shape == (g.heads, n_qb, n_kb)
+    scale = scale if scale > 0 else 1.0 / np.sqrt(g.head_dim)
+    imp = np.zeros((g.heads, n_kb))
+    for qb in range(n_qb):
+        ok = np.array([allowed(qb, kb, g) for kb in range(n_kb)])
+        if not ok.any():
+            continue
+        for h in range(g.heads):
+            logit = S[h, qb, ok] * scale
+            w = np.exp(logit - logit.max())
+            imp[h, ok] += w / w.sum()
+    return imp
+
+
+def group_importance(S: np.ndarray, g: Geometry, kv_frames: int, scale: float = 0.0) -> np.ndarray:
+    """Importance of every visible group of tile_t frames = sum over its blocks.  [heads][groups]."""
+    imp = block_importance(S, g, kv_frames, scale)
+    return imp.reshape(g.heads, kv_frames // g.tile_t, g.nb).sum(axis=-1)
+
+
+class ImportanceCache:
+    """KV cache with importance-based eviction (appendix on KV-cache eviction) as plain lists.
+
+    An entry is one group of tile_t frames.  When new groups do not fit, the cached groups with the
+    lowest importance go (equal importance: the older one first); the arriving groups are never
+    candidates.  Importance comes from `set_importance` (the coarse map of the chunk attended last)
+    and is forgotten at every append: groups that have never been scored count as zero, so without
+    scores the cache behaves like a sliding window.  head-wise: every head decides for itself and
+    heads may see different frames; uniform: importance is summed over heads and all heads share
+    the decision.  Surviving groups stay in temporal order."""
+
+    def __init__(self, capacity_frames: int, tile_t: int, heads: int, uniform: bool):
+        assert capacity_frames % tile_t == 0
+        self.capacity = capacity_frames // tile_t
+        self.tile_t, self.heads, self.uniform = tile_t, heads, uniform
+        # per head: list of [k (tokens_per_group, d), v, importance, birth index]
+        self.groups: list[list[list]] = [[] for _ in range(heads)]
+        self.births = 0
+
+    def set_importance(self, imp: np.ndarray) -> None:
+        """imp[heads][visible groups] in temporal order."""
+        imp = np.asarray(imp, np.float64)
+        assert imp.shape == (self.heads, len(self.groups[0]))
+        if self.uniform:
+            imp = np.broadcast_to(imp.sum(axis=0, keepdims=True), imp.shape)
+        for h in range(self.heads):
+            for e, x in zip(self.groups[h], imp[h]):
+                e[2] = float(x)
+
+    def append(self, k: np.ndarray, v: np.ndarray, n_frames: int) -> None:
+        assert n_frames % self.tile_t == 0
+        n_new = n_frames // self.tile_t
+        per = k.shape[0] // n_new
+        for h in range(self.heads):
+            lst = self.groups[h]
+            for _ in range(max(0, len(lst) + n_new - self.capacity)):
+                victim = min(range(len(lst)), key=lambda i: (lst[i][2], i))     # lowest importance, then oldest
+                lst.pop(victim)
+            for e in lst:
+                e[2] = 0.0
+            for gi in range(n_new):
+                lst.append([np.array(k[gi * per:(gi + 1) * per, h]), np.array(v[gi * per:(gi + 1) * per, h]), 0.0,
+                            self.births + gi])
+        self.births += n_new
+
+    @property
+    def valid_frames(self) -> int:
+        return len(self.groups[0]) * self.tile_t
+
+    def birth_order(self) -> np.ndarray:
+        """[heads][visible groups]: which appended group (counted from 0) each visible group is."""
+        return np.array([[e[3] for e in lst] for lst in self.groups])
+
+    def visible(self):
+        """(K, V) as every head sees them, oldest first: [valid_frames*H*W][heads][d]."""
+        K = np.stack([np.concatenate([e[0] for e in lst], 0) for lst in self.groups], axis=1)
+        V = np.stack([np.concatenate([e[1] for e in lst], 0) for lst in self.groups], axis=1)
+        return K, V
 
 
 def lcsa(q: np.ndarray, k: np.ndarray, v: np.ndarray, g: Geometry, kv_frames: int, rows=None):

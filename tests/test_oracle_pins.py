@@ -395,3 +395,109 @@ def test_temporal_blocks_zero_queries_and_window():
     want = v[toks].astype(np.float64).mean(axis=0)[0]
     q_toks = [f * 48 + r * 8 + c for f in (0, 1) for r in (4, 5) for c in range(4)]
     np.testing.assert_allclose(res["o"][q_toks, 0], np.broadcast_to(want, (16, 8)), rtol=0, atol=1e-14)
+
+
+# ---- importance-based KV eviction (appendix on KV-cache eviction) -------------------------------
+
+def test_importance_unbounded_window_is_softmax_column_mass():
+    """With no window the coarse attention map is a plain row softmax of S/sqrt(d) (library routine);
+    a key block's importance is its column sum."""
+    from scipy.special import softmax
+    g = Geometry(3, 16, 8, 12, 4, 4, 2, -1, -1, 4)
+    rng = np.random.default_rng(11)
+    S = rng.normal(size=(3, 2 * g.nb, 5 * g.nb)) * 7.0
+    want = softmax(S / 4.0, axis=-1).sum(axis=1)
+    np.testing.assert_allclose(oracle.block_importance(S, g, 5), want, rtol=1e-12, atol=1e-14)
+    np.testing.assert_allclose(oracle.block_importance(S, g, 5, scale=0.25), want, rtol=1e-12, atol=1e-14)
+    np.testing.assert_allclose(oracle.group_importance(S, g, 5), want.reshape(3, 5, g.nb).sum(-1), rtol=1e-12)
+    # a different scale is not the same thing
+    assert np.abs(oracle.block_importance(S, g, 5, scale=1.0) - want).max() > 1e-3
+
+
+def test_importance_zero_scores_closed_form_from_hand_written_windows():
+    """S = 0: every query block spreads its unit of attention evenly over the blocks of its window in
+    every visible frame; summed per key block with the hand-enumerated 3x4-tile windows."""
+    sets = {qt: t for m, qt, t in load_window_sets() if m == "truncated"}
+    assert sorted(sets) == list(range(12))
+    g = Geometry(2, 4, 12, 16, 4, 4, 2, 4, 4, 1)
+    kv = 3
+    want = np.zeros(kv * 12)
+    for qf in range(2):
+        for qt in range(12):
+            for f in range(kv):
+                for t in sets[qt]:
+                    want[f * 12 + t] += 1.0 / (kv * len(sets[qt]))
+    got = oracle.block_importance(np.zeros((2, 24, kv * 12)), g, kv)
+    np.testing.assert_allclose(got, np.stack([want, want]), rtol=1e-13)
+
+
+def test_importance_mass_is_conserved_and_stays_in_the_window():
+    g = Geometry(2, 8, 12, 16, 4, 4, 2, 0, 0, 1)          # radius 0: a query tile only sees its own tile position
+    rng = np.random.default_rng(12)
+    kv = 4
+    S = rng.normal(size=(2, 24, kv * 12)) * 3.0
+    imp = oracle.block_importance(S, g, kv)
+    np.testing.assert_allclose(imp.sum(axis=-1), 24.0, rtol=1e-12)      # one unit per query block
+    # closed form: softmax over the kv frames of the same tile position
+    scale = 1.0 / np.sqrt(8)
+    for h in range(2):
+        for t in range(12):
+            want = np.zeros(kv)
+            for qf in range(2):
+                z = np.exp(S[h, qf * 12 + t, t::12] * scale)
+                want += z / z.sum()
+            np.testing.assert_allclose(imp[h, t::12], want, rtol=1e-12)
+
+
+def _groups(rng, n, per=6, heads=2, d=4):
+    return rng.normal(size=(n * per, heads, d)), rng.normal(size=(n * per, heads, d))
+
+
+@pytest.mark.parametrize("uniform", [False, True])
+def test_importance_cache_without_scores_is_the_sliding_window(uniform):
+    rng = np.random.default_rng(13)
+    a = oracle.ImportanceCache(6, 1, 2, uniform)
+    b = oracle.SlidingWindowCache(6)
+    for n in (2, 1, 3, 2, 6, 1, 4):
+        k, v = _groups(rng, n)
+        a.append(k, v, n)
+        b.append(k, v, n)
+        assert a.valid_frames == b.valid_frames
+        for x, y in zip(a.visible(), b.visible()):
+            np.testing.assert_array_equal(x, y)
+
+
+def test_importance_cache_head_wise_and_uniform_decisions():
+    rng = np.random.default_rng(14)
+    imp = np.array([[3.0, 1.0, 2.0, 5.0], [0.0, 9.0, 9.0, 1.0]])
+    want = {False: [[0, 3, 4, 5], [1, 2, 4, 5]],          # every head drops its own two weakest groups
+            True: [[1, 2, 4, 5], [1, 2, 4, 5]]}           # sums 3, 10, 11, 6: groups 0 and 3 go for both heads
+    for uniform in (False, True):
+        c = oracle.ImportanceCache(4, 1, 2, uniform)
+        k, v = _groups(rng, 4)
+        c.append(k, v, 4)
+        c.set_importance(imp)
+        k2, v2 = _groups(rng, 2)
+        c.append(k2, v2, 2)
+        assert c.birth_order().tolist() == want[uniform]
+        K, V = c.visible()
+        allk = np.concatenate([k, k2])
+        for h in range(2):
+            np.testing.assert_array_equal(K[:, h], np.concatenate([allk[b * 6:(b + 1) * 6, h] for b in want[uniform][h]]))
+        # scores are forgotten at an append: the next eviction without new scores takes the oldest
+        k3, v3 = _groups(rng, 1)
+        c.append(k3, v3, 1)
+        assert c.birth_order().tolist() == [w[1:] + [6] for w in want[uniform]]
+
+
+def test_importance_cache_ties_evict_the_older_group_and_new_groups_are_safe():
+    rng = np.random.default_rng(15)
+    c = oracle.ImportanceCache(6, 2, 1, False)            # groups of two frames, room for three groups
+    for _ in range(3):
+        k, v = _groups(rng, 1, per=12, heads=1)
+        c.append(k, v, 2)
+    c.set_importance(np.array([[2.0, 2.0, 7.0]]))
+    k, v = _groups(rng, 2, per=12, heads=1)
+    c.append(k, v, 4)                                     # two groups arrive, two must go: the tied pair, never the arrivals
+    assert c.birth_order().tolist() == [[2, 3, 4]]
+    assert c.valid_frames == 6
