@@ -51,6 +51,8 @@ def main() -> int:
     ap.add_argument("--blocks", default="", help="block shape t,h,w overriding the workload's 1,tile_h,tile_w (e.g. 2,8,8: the paper's partition)")
     ap.add_argument("--grid", default="", help="latent grid h,w overriding the workload's (e.g. 96,168: a 1536x2688 video)")
     ap.add_argument("--cache-frames", type=int, default=0, help="override the sliding-window capacity in frames")
+    ap.add_argument("--eviction", default="sliding", choices=["sliding", "headwise", "uniform"],
+                    help="KV-cache eviction: the paper's default sliding window, or importance-based (adds lcsa_block_importance to every layer call)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device-to-device copy (reference point for HBM byte counters)")
@@ -84,6 +86,8 @@ def main() -> int:
     g = B.Geom(w.heads, w.head_dim, w.grid_h, w.grid_w, w.tile_h, w.tile_w, w.q_frames, w.cache_frames,
                radius, radius, topk, dtype=B.LCSA_BF16, tile_t=tile_t)
     n_qb = g.n_qb
+    policy = {"sliding": B.LCSA_EVICT_SLIDING, "headwise": B.LCSA_EVICT_IMPORTANCE_HEADWISE,
+              "uniform": B.LCSA_EVICT_IMPORTANCE_UNIFORM}[args.eviction]
 
     def dev(x):
         return torch.from_numpy(wl.bf16_bits(x).view(np.int16)).view(torch.bfloat16).cuda()
@@ -100,6 +104,8 @@ def main() -> int:
     with ThreadPoolExecutor(max_workers=min(8, os.cpu_count() or 1)) as pool:
         for layer, chunks in enumerate(pool.map(gen, range(n_layers))):
             cache = B.lcsa_cache_init(g)
+            if policy != B.LCSA_EVICT_SLIDING:
+                B.lcsa_cache_set_eviction(cache, policy)
             dchunks = [tuple(dev(x) for x in c) for c in chunks]
             # fill the ring with all chunks of the stream; a timed step then re-appends them in turn,
             # so the window always holds the same frames (a static scene) and every append evicts
@@ -129,6 +135,9 @@ def main() -> int:
         B.lcsa_sparse_attn_fwd(g, q, L["cache"], L["sel_idx"], L["sel_cnt"], L["o"])
         if attn_ev: attn_ev[1].record()
         if ev: ev[3].record()
+        if policy != B.LCSA_EVICT_SLIDING:
+            B.lcsa_block_importance(g, L["pq"], L["cache"])     # scores the visible groups for the next append
+        if ev: ev[5].record()
 
     if args.calibrate_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
@@ -158,13 +167,13 @@ def main() -> int:
     attn_ms = np.array([[e0.elapsed_time(e1) for (e0, e1) in step] for step in attn_ev])
 
     # ---- untimed breakdown pass: events between the four calls ------------------------------------
-    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in layers]
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in layers]
     for L, e in zip(layers, ev):
         e[4].record()
         layer_call(L, e)
     torch.cuda.synchronize()
-    brk = np.array([[e[4].elapsed_time(e[0]), e[0].elapsed_time(e[1]), e[1].elapsed_time(e[2]), e[2].elapsed_time(e[3])]
-                    for e in ev]).mean(axis=0)
+    brk = np.array([[e[4].elapsed_time(e[0]), e[0].elapsed_time(e[1]), e[1].elapsed_time(e[2]), e[2].elapsed_time(e[3]),
+                     e[3].elapsed_time(e[5])] for e in ev]).mean(axis=0)
 
     # ---- what this chip sustains on trivial loops, quoted beside the nominal peaks (outside the timed region):
     # back-to-back bf16 matrix instructions on registers, and a 1 GiB device-to-device copy
@@ -235,10 +244,12 @@ def main() -> int:
         "config": {"workload": WORKLOAD_TEXT[args.workload], "heads": g.heads, "head_dim": g.head_dim,
                    "layers_per_step": n_layers, "q_tokens": tok_new, "kv_tokens": w.cache_frames * w.tokens_per_frame,
                    "block_shape": [tile_t, w.tile_h, w.tile_w], "blocks_per_group": g.nb, "query_blocks": n_qb,
-                   "grid": [w.grid_h, w.grid_w], "cache_frames": w.cache_frames, "topk": topk, "radius": radius},
+                   "grid": [w.grid_h, w.grid_w], "cache_frames": w.cache_frames, "topk": topk, "radius": radius,
+                   "eviction": args.eviction},
         "effective_tflops_whole_path": round(useful_flop / (ms_per_layer * 1e-3) / 1e12, 2),
         "kernel_ms_per_layer": {"kv_cache_append": round(float(brk[0]), 5), "pool_blocks": round(float(brk[1]), 5),
-                                "select_blocks": round(float(brk[2]), 5), "sparse_attn_fwd": round(attn_avg_ms, 5)},
+                                "select_blocks": round(float(brk[2]), 5), "sparse_attn_fwd": round(attn_avg_ms, 5),
+                                **({"block_importance": round(float(brk[4]), 5)} if policy != B.LCSA_EVICT_SLIDING else {})},
         "hbm_gbs": {"kv_cache_append": round(append_bytes / (brk[0] * 1e-3) / 1e9, 1),
                     "pool_blocks": round(pool_bytes / (brk[1] * 1e-3) / 1e9, 1),
                     "select_blocks": round(select_bytes / (brk[2] * 1e-3) / 1e9, 1)},
@@ -248,7 +259,7 @@ def main() -> int:
                            "device_copy_gbs": round(copy_gbs, 1)},
         "roofline": {"kernel": "attn_mfma_kernel", "bound": "mfma", "achieved": round(achieved, 2),
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
-                     "traffic": ATTN_TRAFFIC_BYTES.get((args.workload, topk)) if not (args.blocks or args.grid or args.cache_frames) and args.radius is None else None,
+                     "traffic": ATTN_TRAFFIC_BYTES.get((args.workload, topk)) if not (args.blocks or args.grid or args.cache_frames) and args.radius is None and policy == B.LCSA_EVICT_SLIDING else None,
                      "flop_per_launch_useful": useful_flop, "flop_per_launch_issued": issued_flop,
                      "issued_tflops": round(issued_flop / (attn_avg_ms * 1e-3) / 1e12, 2),
                      "avg_launch_ms": round(attn_avg_ms, 5), "min_launch_ms": round(float(attn_ms.min()), 5)},

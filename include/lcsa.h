@@ -51,6 +51,9 @@ typedef enum lcsa_status {
 
 enum { LCSA_F32 = 0, LCSA_BF16 = 1 };
 enum { LCSA_WINDOW_TRUNCATED = 0, LCSA_WINDOW_PRESERVED = 1 };
+/* KV-cache eviction (appendix on KV-cache eviction): sliding window (the paper's default), or by
+ * importance, decided per head or once for all heads of the layer */
+enum { LCSA_EVICT_SLIDING = 0, LCSA_EVICT_IMPORTANCE_HEADWISE = 1, LCSA_EVICT_IMPORTANCE_UNIFORM = 2 };
 
 /* Problem geometry.  Plain data, passed by pointer, validated on every call. */
 typedef struct lcsa_geom {
@@ -96,17 +99,49 @@ int32_t lcsa_cache_valid_frames(const lcsa_cache *cache);
  * group that holds visible frame f (0 = oldest) is row lcsa_cache_frame_slot(cache, f)*nb + tile.
  */
 const float *lcsa_cache_pooled_k_device(const lcsa_cache *cache);
-int32_t lcsa_cache_frame_slot(const lcsa_cache *cache, int32_t frame);
+int32_t lcsa_cache_frame_slot(const lcsa_cache *cache, int32_t frame);   /* sliding-window policy only */
 
 /*
  * Appends the keys and values of n_frames new frames (device, raster order, the cache's
- * dtype, shared strides) and evicts the oldest frames beyond the capacity: sliding-window
- * eviction, the paper's default.  Also stores the block means of the new keys (Sec. 3.2
+ * dtype, shared strides) and evicts frames beyond the capacity: the oldest ones under
+ * sliding-window eviction, the paper's default (see lcsa_cache_set_eviction for the alternative).  Also stores the block means of the new keys (Sec. 3.2
  * average pooling) for lcsa_select_blocks.  1 <= n_frames <= cache_frames, a multiple of tile_t.
  */
 int32_t lcsa_kv_cache_append(lcsa_cache *cache, const void *k, const void *v,
                              int64_t stride_tok, int64_t stride_head,
                              int32_t n_frames, void *stream);
+
+/* ---- importance-based eviction (appendix on KV-cache eviction; a preliminary exploration there) --- */
+
+/*
+ * Chooses how lcsa_kv_cache_append makes room once the cache is full.  Allowed only while the
+ * cache is empty (after init or reset), else LCSA_EINVAL.  Under an importance policy an entry
+ * is one group of tile_t frames; an append that does not fit drops the visible groups with the
+ * lowest importance (equal importance: the older group first; arriving groups are never
+ * candidates), surviving groups stay in temporal order (key-block ids count in that order), and
+ * the scores are forgotten.  Groups that were never scored count as 0, so without calls to
+ * lcsa_block_importance the cache behaves like the sliding window.  HEADWISE: every head decides
+ * for itself (heads may then hold different frames); UNIFORM: by the sum over heads, one decision.
+ * The decision is taken on the device in stream order.  At most 64 groups of capacity
+ * (LCSA_EUNSUPPORTED beyond).
+ */
+int32_t lcsa_cache_set_eviction(lcsa_cache *cache, int32_t policy);
+int32_t lcsa_cache_eviction(const lcsa_cache *cache);
+/*
+ * Scores the visible groups from the coarse block-to-block attention map of the current chunk:
+ * for every (head, query block) the softmax (eq. 1; scale <= 0 selects 1/sqrt(head_dim)) of the
+ * pooled-Q . pooled-K scores (Sec. 3.2) over the key blocks inside the spatial window (Sec. 3.3);
+ * the importance of a group is the attention its blocks receive, summed over the chunk's query
+ * blocks.  Result: device float [heads][cache_frames/tile_t] indexed by visible group (0 =
+ * oldest), kept inside the cache (lcsa_cache_importance_device) for the next append.  Call it
+ * after the chunk's own append, with the pooled queries lcsa_select_blocks was given.
+ */
+int32_t lcsa_block_importance(const lcsa_geom *geom, const float *pooled_q, lcsa_cache *cache, float scale, void *stream);
+/* Inspection helpers for tests: the scores above, and under an importance policy the device table
+ * int32 [heads][cache_frames/tile_t], visible group (0 = oldest) -> slot (NULL under the sliding window,
+ * where lcsa_cache_frame_slot answers on the host). */
+const float *lcsa_cache_importance_device(const lcsa_cache *cache);
+const int32_t *lcsa_cache_order_device(const lcsa_cache *cache);
 
 /* ---- block pooling (Sec. 3.2: average pooling inside each block) ------------------------------ */
 

@@ -17,6 +17,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 # LCSA_LIBRARY may name another build of the same library (e.g. an experimental kernel variant)
 LIB_PATH = os.environ.get("LCSA_LIBRARY") or os.path.join(_HERE, "liblcsa.so")
 
+LCSA_EVICT_SLIDING, LCSA_EVICT_IMPORTANCE_HEADWISE, LCSA_EVICT_IMPORTANCE_UNIFORM = 0, 1, 2
 LCSA_F32, LCSA_BF16 = 0, 1
 WINDOW_TRUNCATED, WINDOW_PRESERVED = 0, 1
 
@@ -98,12 +99,19 @@ def lib():
         L.lcsa_select_blocks.argtypes = [_gp, _vp, _vp, _vp, _vp, _vp, _vp]
         L.lcsa_sparse_attn_fwd.argtypes = [_gp, _vp, _i64, _i64, _vp, _vp, _vp, _vp, _i64, _i64, _vp, _f32, _vp]
         L.lcsa_probe_mfma_bf16.argtypes = [_vp, _i32, _i32, _vp]
+        L.lcsa_cache_set_eviction.argtypes = [_vp, _i32]
+        L.lcsa_cache_eviction.argtypes = [_vp]
+        L.lcsa_block_importance.argtypes = [_gp, _vp, _vp, _f32, _vp]
+        L.lcsa_cache_importance_device.argtypes = [_vp]
+        L.lcsa_cache_importance_device.restype = _vp
+        L.lcsa_cache_order_device.argtypes = [_vp]
+        L.lcsa_cache_order_device.restype = _vp
         L.lcsa_status_string.restype = ctypes.c_char_p
         L.lcsa_status_string.argtypes = [_i32]
         L.lcsa_last_hip_error.restype = ctypes.c_char_p
         for f in ("lcsa_cache_init", "lcsa_cache_reset", "lcsa_cache_valid_frames", "lcsa_cache_frame_slot",
                   "lcsa_kv_cache_append", "lcsa_pool_blocks", "lcsa_select_blocks", "lcsa_sparse_attn_fwd",
-                  "lcsa_probe_mfma_bf16"):
+                  "lcsa_probe_mfma_bf16", "lcsa_cache_set_eviction", "lcsa_cache_eviction", "lcsa_block_importance"):
             getattr(L, f).restype = _i32
         _lib = L
     return _lib
@@ -186,6 +194,42 @@ def lcsa_cache_frame_slot(cache: Cache, frame: int) -> int:
     if s < 0:
         _check(s, "lcsa_cache_frame_slot")
     return s
+
+
+def lcsa_cache_set_eviction(cache: Cache, policy: int) -> None:
+    _check(lib().lcsa_cache_set_eviction(cache.handle, policy), "lcsa_cache_set_eviction")
+
+
+def lcsa_cache_eviction(cache: Cache) -> int:
+    return lib().lcsa_cache_eviction(cache.handle)
+
+
+def lcsa_block_importance(geom: Geom, pooled_q: torch.Tensor, cache: Cache, scale: float = 0.0, stream=None) -> torch.Tensor:
+    """Scores the visible groups for the next append; returns the view lcsa_cache_importance gives."""
+    assert pooled_q.is_contiguous() and pooled_q.dtype == torch.float32
+    assert pooled_q.shape == (geom.heads, geom.n_qb, geom.head_dim)
+    g = geom.c()
+    _check(lib().lcsa_block_importance(ctypes.byref(g), pooled_q.data_ptr(), cache.handle, scale, _stream(stream)),
+           "lcsa_block_importance")
+    return lcsa_cache_importance(cache)
+
+
+def _cache_view(cache: Cache, ptr: int, dtype) -> torch.Tensor:
+    g = cache.geom
+    n = g.heads * (g.cache_frames // g.tile_t)
+    off = ptr - cache.storage.data_ptr()
+    return cache.storage[off:off + 4 * n].view(dtype).view(g.heads, g.cache_frames // g.tile_t)
+
+
+def lcsa_cache_importance(cache: Cache) -> torch.Tensor:
+    """float view [heads][cache_frames/tile_t] over the cache storage: importance by visible group (0 = oldest)."""
+    return _cache_view(cache, lib().lcsa_cache_importance_device(cache.handle), torch.float32)
+
+
+def lcsa_cache_order(cache: Cache) -> torch.Tensor | None:
+    """int32 view [heads][cache_frames/tile_t]: visible group -> slot, per head; None under the sliding window."""
+    ptr = lib().lcsa_cache_order_device(cache.handle)
+    return _cache_view(cache, ptr, torch.int32) if ptr else None
 
 
 def lcsa_cache_pooled_k(cache: Cache) -> torch.Tensor:

@@ -84,7 +84,7 @@ __global__ __launch_bounds__(64 * kWaves) void attn_generic_kernel(
             const int kb = sel[b];
             const int f = kb / g.nb, kt = kb - f * g.nb, kby = kt / g.tx, kbx = kt - kby * g.tx;
             const int vh = min(g.th, g.H - kby * g.th), vw = min(g.tw, g.W - kbx * g.tw);
-            const int slot = slot_of_frame(c.start, g.cap, f);
+            const int slot = cache_slot(c, g, head, f);
             const int64_t tbase = (((int64_t)head * g.cap + slot) * g.nb + kt) * g.bt * g.d;
             for (int base = 0; base < g.bt; base += 64) {
                 const int key = base + lane;

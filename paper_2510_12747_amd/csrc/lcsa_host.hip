@@ -14,6 +14,11 @@ struct lcsa_cache {
     KGeom kg;
     KCache kc;
     size_t bytes;
+    int32_t policy;        // LCSA_EVICT_*
+    int32_t *order;        // device [heads][cap]: visible group -> slot (importance-based policies)
+    float *importance;     // device [heads][cap]: importance of the visible groups, from lcsa_block_importance
+    float *row_group;      // device [heads][n_qb][cap]: scratch of lcsa_block_importance
+    bool scored;           // `importance` was computed since the last append (the scores are used once)
 };
 
 namespace {
@@ -68,7 +73,7 @@ bool same_geom(const lcsa_geom *a, const lcsa_geom &b) {
            a->cache_frames == b.cache_frames && a->dtype == b.dtype;
 }
 
-struct Layout { size_t k_off, v_off, pooled_off, total; };
+struct Layout { size_t k_off, v_off, pooled_off, order_off, imp_off, row_group_off, total; };
 
 Layout cache_layout(const KGeom &k) {
     const size_t elt = k.bf16 ? 2 : 4;
@@ -78,7 +83,10 @@ Layout cache_layout(const KGeom &k) {
     l.k_off = 0;
     l.v_off = kv;
     l.pooled_off = 2 * kv;
-    l.total = 2 * kv + align_up(tiles * k.d * sizeof(float), 256);
+    l.order_off = l.pooled_off + align_up(tiles * k.d * sizeof(float), 256);
+    l.imp_off = l.order_off + align_up((size_t)k.heads * k.cap * sizeof(int32_t), 256);
+    l.row_group_off = l.imp_off + align_up((size_t)k.heads * k.cap * sizeof(float), 256);
+    l.total = l.row_group_off + align_up((size_t)k.heads * k.q_groups * k.nb * k.cap * sizeof(float), 256);
     return l;
 }
 
@@ -115,6 +123,12 @@ int32_t lcsa_cache_init(lcsa_cache **out, const lcsa_geom *geom, void *device_me
     c->kc.start = 0;
     c->kc.valid = 0;
     c->kc.mfma_layout = kg.bf16 && kg.d == 128 && kg.bt == 128;
+    c->kc.order = nullptr;
+    c->policy = LCSA_EVICT_SLIDING;
+    c->order = (int32_t *)(base + l.order_off);
+    c->importance = (float *)(base + l.imp_off);
+    c->row_group = (float *)(base + l.row_group_off);
+    c->scored = false;
     *out = c;
     return LCSA_OK;
 }
@@ -123,10 +137,28 @@ int32_t lcsa_cache_reset(lcsa_cache *cache) {
     if (!cache) return LCSA_EINVAL;
     cache->kc.start = 0;
     cache->kc.valid = 0;
+    cache->scored = false;
     return LCSA_OK;
 }
 
 void lcsa_cache_free(lcsa_cache *cache) { delete cache; }
+
+int32_t lcsa_cache_set_eviction(lcsa_cache *cache, int32_t policy) {
+    if (!cache || cache->kc.valid != 0) return LCSA_EINVAL;
+    if (policy != LCSA_EVICT_SLIDING && policy != LCSA_EVICT_IMPORTANCE_HEADWISE && policy != LCSA_EVICT_IMPORTANCE_UNIFORM)
+        return LCSA_EINVAL;
+    if (policy != LCSA_EVICT_SLIDING && cache->kg.cap > kMaxEvictGroups) return LCSA_EUNSUPPORTED;
+    cache->policy = policy;
+    cache->kc.order = policy == LCSA_EVICT_SLIDING ? nullptr : cache->order;
+    cache->kc.start = 0;
+    return LCSA_OK;
+}
+
+int32_t lcsa_cache_eviction(const lcsa_cache *cache) { return cache ? cache->policy : (int32_t)LCSA_EINVAL; }
+
+const int32_t *lcsa_cache_order_device(const lcsa_cache *cache) { return cache ? cache->kc.order : nullptr; }
+
+const float *lcsa_cache_importance_device(const lcsa_cache *cache) { return cache ? cache->importance : nullptr; }
 
 int32_t lcsa_cache_valid_frames(const lcsa_cache *cache) {
     return cache ? cache->kc.valid * cache->kg.tt : (int32_t)LCSA_EINVAL;
@@ -136,6 +168,7 @@ const float *lcsa_cache_pooled_k_device(const lcsa_cache *cache) { return cache 
 
 int32_t lcsa_cache_frame_slot(const lcsa_cache *cache, int32_t frame) {
     if (!cache || frame < 0 || frame >= cache->kc.valid * cache->kg.tt) return LCSA_EINVAL;
+    if (cache->policy != LCSA_EVICT_SLIDING) return LCSA_EINVAL;      // per head, on the device: lcsa_cache_order_device
     return slot_of_frame(cache->kc.start, cache->kg.cap, frame / cache->kg.tt);
 }
 
@@ -148,6 +181,19 @@ int32_t lcsa_kv_cache_append(lcsa_cache *cache, const void *k, const void *v,
     if ((int64_t)n_frames * kg.H * kg.W > (1ll << 30)) return LCSA_EINVAL;
     KCache &kc = cache->kc;
     const int n_groups = n_frames / kg.tt;
+    if (cache->policy != LCSA_EVICT_SLIDING) {
+        // The least important visible groups make room (per head, or for all heads alike); the table of
+        // slots is rewritten on the device, in stream order, before the tiles are written.
+        const int evict = kc.valid + n_groups > kg.cap ? kc.valid + n_groups - kg.cap : 0;
+        hipError_t e = launch_evict(kg, cache->order, cache->importance, kc.valid, n_groups, evict,
+                                    cache->policy == LCSA_EVICT_IMPORTANCE_UNIFORM, cache->scored, (hipStream_t)stream);
+        if (e != hipSuccess) return hip_status(e);
+        cache->scored = false;
+        e = launch_append(kg, kc, k, v, stride_tok, stride_head, n_groups, kc.valid - evict, (hipStream_t)stream);
+        if (e != hipSuccess) return hip_status(e);
+        kc.valid = kc.valid - evict + n_groups;
+        return LCSA_OK;
+    }
     // New groups go into the slots right after the newest one; once the ring is full those are the
     // slots of the oldest groups, which thereby leave the window.
     const int first = slot_of_frame(kc.start, kg.cap, kc.valid);   // start + valid < 2*cap
@@ -177,6 +223,20 @@ int32_t lcsa_select_blocks(const lcsa_geom *geom, const float *pooled_q, const l
     const int mc = max_candidates(kg, cache->kc.valid);
     if (mc > 8192) return LCSA_EUNSUPPORTED;
     return hip_status(launch_select(kg, cache->kc, pooled_q, sel_idx, sel_cnt, gap, mc, (hipStream_t)stream));
+}
+
+int32_t lcsa_block_importance(const lcsa_geom *geom, const float *pooled_q, lcsa_cache *cache, float scale, void *stream) {
+    if (!geom_ok(geom) || !cache || !pooled_q) return LCSA_EINVAL;
+    if (!same_geom(geom, cache->geom)) return LCSA_EINVAL;
+    if (cache->kc.valid * geom->tile_t < geom->q_frames) return LCSA_EINVAL;
+    KGeom kg = derive(*geom);   // the window may differ from the cache's own copy
+    const int mc = max_candidates(kg, cache->kc.valid);
+    if (mc > 8192 || kg.cap > 1024) return LCSA_EUNSUPPORTED;
+    if (!(scale > 0.f)) scale = 1.0f / sqrtf((float)kg.d);
+    const hipError_t e = launch_importance(kg, cache->kc, pooled_q, scale, cache->row_group, cache->importance, mc,
+                                           (hipStream_t)stream);
+    if (e == hipSuccess) cache->scored = true;
+    return hip_status(e);
 }
 
 int32_t lcsa_sparse_attn_fwd(const lcsa_geom *geom, const void *q, int64_t q_stride_tok, int64_t q_stride_head,

@@ -32,14 +32,22 @@ struct KGeom {
 struct KCache {
     void *k, *v;
     float *pooled;
-    int start;   // ring slot of the oldest visible group
+    int start;   // ring slot of the oldest visible group (sliding-window eviction)
     int valid;   // visible groups
     int mfma_layout;
+    // importance-based eviction: device table [heads][cap], visible group (0 = oldest) -> slot, per head;
+    // null under sliding-window eviction, where the slot follows from `start`
+    const int32_t *order;
 };
 
 __host__ __device__ inline int slot_of_frame(int start, int cap, int f) {
     int s = start + f;
     return s >= cap ? s - cap : s;
+}
+
+// Slot that holds visible group f (0 = oldest) of a head.
+__device__ inline int cache_slot(const KCache &c, const KGeom &g, int head, int f) {
+    return c.order ? c.order[head * g.cap + f] : slot_of_frame(c.start, g.cap, f);
 }
 
 // Block token i -> (frame within the group, row, col inside the tile) of a tile clipped to vh x vw.
@@ -62,10 +70,25 @@ __host__ __device__ inline int64_t raster_token(const KGeom &g, int group, int f
 hipError_t launch_pool(const KGeom &g, const void *x, int64_t stride_tok, int64_t stride_head,
                        int n_groups, float *pooled, hipStream_t stream);
 
-// Writes n_groups groups of frames into ring slots first_slot.. (mod cap): tiles of K, V and pooled K.
+// Writes n_groups groups of frames: tiles of K, V and pooled K.  Sliding window (c.order null): into
+// ring slots first.. (mod cap).  Importance-based eviction: group i into the slot that c.order gives
+// visible group first + i of each head.
 hipError_t launch_append(const KGeom &g, const KCache &c, const void *k, const void *v,
-                         int64_t stride_tok, int64_t stride_head, int n_groups, int first_slot,
+                         int64_t stride_tok, int64_t stride_head, int n_groups, int first,
                          hipStream_t stream);
+
+// Importance of the visible groups from the coarse attention map of one chunk (appendix on KV-cache
+// eviction): imp[heads][cap] by visible group; row_group is scratch [heads][n_qb][cap].
+hipError_t launch_importance(const KGeom &g, const KCache &c, const float *pooled_q, float scale,
+                             float *row_group, float *imp, int max_cand, hipStream_t stream);
+
+// Importance-based eviction before an append of n_new groups: drops the n_evict least important of the
+// `valid` visible groups of every head (uniform: by the sum over heads), gives the arrivals the free
+// slots, and rewrites order[heads][cap].  scored = false: imp is not read and every group counts as 0
+// (oldest first).  cap <= kMaxEvictGroups.
+constexpr int kMaxEvictGroups = 64;
+hipError_t launch_evict(const KGeom &g, int32_t *order, const float *imp, int valid, int n_new, int n_evict,
+                        bool uniform, bool scored, hipStream_t stream);
 
 hipError_t launch_select(const KGeom &g, const KCache &c, const float *pooled_q,
                          int32_t *sel_idx, int32_t *sel_cnt, float *gap, int max_cand,
@@ -105,3 +128,4 @@ __host__ __device__ inline void axis_window(int b, int tile, int n, int radius, 
 }
 
 } // namespace lcsa
+

@@ -107,11 +107,11 @@ __global__ __launch_bounds__(kThreads) void pool_kernel(KGeom g, const char *x, 
 // pooled K written beside them.                                      grid (n_groups*nb, heads)
 template <int VEC>
 __global__ __launch_bounds__(kThreads) void append_generic_kernel(KGeom g, KCache c, const char *k, const char *v,
-                                                                  int64_t st, int64_t sh, int first_slot) {
+                                                                  int64_t st, int64_t sh, int first) {
     __shared__ float red[kThreads * VEC];
     const int block = blockIdx.x, head = blockIdx.y;
     const TileRef t = tile_ref(g, block);
-    const int slot = (first_slot + t.group) % g.cap;
+    const int slot = c.order ? c.order[head * g.cap + first + t.group] : (first + t.group) % g.cap;
     const int tile = block - t.group * g.nb;
     constexpr int ELT = 16 / VEC;
     const int64_t tile_index = ((int64_t)head * g.cap + slot) * g.nb + tile;
@@ -167,12 +167,12 @@ __device__ inline uint32_t bf16_bits_to_half_bits(uint32_t b) {
 constexpr int kVPitchWords = 65;   // LDS pitch of a staged V token row (128 bf16 = 64 words, +1)
 
 __global__ __launch_bounds__(kThreads) void append_mfma_kernel(KGeom g, KCache c, const char *k, const char *v,
-                                                               int64_t st, int64_t sh, int first_slot) {
+                                                               int64_t st, int64_t sh, int first) {
     __shared__ float red[16 * 128];
     __shared__ uint32_t vs[128 * kVPitchWords];
     const int block = blockIdx.x, head = blockIdx.y;
     const TileRef t = tile_ref(g, block);
-    const int slot = (first_slot + t.group) % g.cap;
+    const int slot = c.order ? c.order[head * g.cap + first + t.group] : (first + t.group) % g.cap;
     const int tile = block - t.group * g.nb;
     const int64_t tile_index = ((int64_t)head * g.cap + slot) * g.nb + tile;
     char *kt = (char *)c.k + tile_index * (128 * 256);
@@ -232,15 +232,15 @@ hipError_t launch_pool(const KGeom &g, const void *x, int64_t stride_tok, int64_
 }
 
 hipError_t launch_append(const KGeom &g, const KCache &c, const void *k, const void *v,
-                         int64_t stride_tok, int64_t stride_head, int n_groups, int first_slot,
+                         int64_t stride_tok, int64_t stride_head, int n_groups, int first,
                          hipStream_t stream) {
     dim3 grid(n_groups * g.nb, g.heads);
     if (c.mfma_layout)
-        append_mfma_kernel<<<grid, kThreads, 0, stream>>>(g, c, (const char *)k, (const char *)v, stride_tok, stride_head, first_slot);
+        append_mfma_kernel<<<grid, kThreads, 0, stream>>>(g, c, (const char *)k, (const char *)v, stride_tok, stride_head, first);
     else if (g.bf16)
-        append_generic_kernel<8><<<grid, kThreads, 0, stream>>>(g, c, (const char *)k, (const char *)v, stride_tok, stride_head, first_slot);
+        append_generic_kernel<8><<<grid, kThreads, 0, stream>>>(g, c, (const char *)k, (const char *)v, stride_tok, stride_head, first);
     else
-        append_generic_kernel<4><<<grid, kThreads, 0, stream>>>(g, c, (const char *)k, (const char *)v, stride_tok, stride_head, first_slot);
+        append_generic_kernel<4><<<grid, kThreads, 0, stream>>>(g, c, (const char *)k, (const char *)v, stride_tok, stride_head, first);
     return hipGetLastError();
 }
 

@@ -59,7 +59,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(KGeom g, KCache c, 
             if (ci < n) {
                 int f;
                 const int t = tile_of(ci, f);
-                const int slot = slot_of_frame(c.start, g.cap, f);
+                const int slot = cache_slot(c, g, head, f);
                 const float4 *kr = (const float4 *)(c.pooled + (((int64_t)head * g.cap + slot) * g.nb + t) * g.d);
                 for (int e0 = part; e0 < n4; e0 += 4 * 16) {
                     float4 kk[16];

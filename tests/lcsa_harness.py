@@ -106,12 +106,18 @@ def check_outputs(o_gpu: torch.Tensor, q, K, V, og, kv_frames, sel_idx, sel_cnt,
 class Pipeline:
     """One layer's state on both sides: the library's cache and the oracle's list model."""
 
-    def __init__(self, w: wl.Workload, layer: int = 0, layout: str = "thd", **geom_kw):
+    def __init__(self, w: wl.Workload, layer: int = 0, layout: str = "thd", eviction: int = B.LCSA_EVICT_SLIDING, **geom_kw):
         self.w, self.layout = w, layout
         self.g, self.og = geoms(w, **geom_kw)
         self.stream = wl.ChunkStream(w, layer)
         self.cache = B.lcsa_cache_init(self.g)
-        self.model = oracle.SlidingWindowCache(w.cache_frames)
+        self.eviction = eviction
+        if eviction == B.LCSA_EVICT_SLIDING:
+            self.model = oracle.SlidingWindowCache(w.cache_frames)
+        else:
+            B.lcsa_cache_set_eviction(self.cache, eviction)
+            self.model = oracle.ImportanceCache(w.cache_frames, self.g.tile_t, w.heads,
+                                                eviction == B.LCSA_EVICT_IMPORTANCE_UNIFORM)
         self.chunk = 0
 
     def feed(self, q=None, k=None, v=None):
@@ -130,9 +136,55 @@ class Pipeline:
         want = oracle.pool(K, self.og, self.model.valid_frames)
         got = B.lcsa_cache_pooled_k(self.cache).cpu().numpy()
         nb, tt = self.g.nb, self.g.tile_t
+        order = B.lcsa_cache_order(self.cache)
+        order = None if order is None else order.cpu().numpy()
         for grp in range(self.model.valid_frames // tt):
-            s = B.lcsa_cache_frame_slot(self.cache, grp * tt)
-            np.testing.assert_allclose(got[:, s * nb:(s + 1) * nb], want[:, grp * nb:(grp + 1) * nb], rtol=0, atol=tol)
+            if order is None:
+                s = B.lcsa_cache_frame_slot(self.cache, grp * tt)
+                np.testing.assert_allclose(got[:, s * nb:(s + 1) * nb], want[:, grp * nb:(grp + 1) * nb], rtol=0, atol=tol)
+            else:       # every head has its own table of slots (and may hold different frames)
+                for h in range(self.g.heads):
+                    s = int(order[h, grp])
+                    np.testing.assert_allclose(got[h, s * nb:(s + 1) * nb], want[h, grp * nb:(grp + 1) * nb], rtol=0, atol=tol)
+        if order is not None:   # a head's visible groups sit in distinct slots
+            n = self.model.valid_frames // tt
+            assert all(len(set(order[h, :n])) == n and order[h, :n].max() < self.g.cache_frames // tt for h in range(self.g.heads))
+
+    def score_groups(self, q, qd, rtol=2e-4):
+        """lcsa_block_importance against the oracle's importance of the visible groups; the oracle's
+        values then drive the model's next eviction.  Returns the oracle's importance."""
+        pq = B.lcsa_pool_blocks(self.g, qd, self.g.q_frames)
+        got = B.lcsa_block_importance(self.g, pq, self.cache).cpu().numpy()
+        kvf = self.model.valid_frames
+        K, _ = self.model.visible()
+        S = oracle.scores(oracle.pool(q, self.og, self.g.q_frames), oracle.pool(K, self.og, kvf))
+        want = oracle.group_importance(S, self.og, kvf)
+        n = kvf // self.g.tile_t
+        np.testing.assert_allclose(got[:, :n], want, rtol=rtol, atol=1e-5)
+        assert (got[:, n:] == 0).all()
+        np.testing.assert_allclose(got.sum(axis=1), self.g.n_qb, rtol=1e-4)     # one unit of attention per query block
+        if isinstance(self.model, oracle.ImportanceCache):
+            # Which groups go at the next append is decided by these numbers.  Where the oracle's own decision
+            # hinges on a near-tie (relative margin below 2e-3, far above the fp32 error checked above) the model
+            # follows the kernel's numbers, as for near-ties of the block selection; such cases are reported.
+            cap, n_new = self.g.cache_frames // self.g.tile_t, self.g.q_frames // self.g.tile_t
+            n_evict = max(0, n + n_new - cap)
+            feed, near = want.copy(), 0
+            if n_evict:
+                uniform = self.eviction == B.LCSA_EVICT_IMPORTANCE_UNIFORM
+                srt = np.sort(want.sum(axis=0, keepdims=True) if uniform else want, axis=1)
+                tie = (srt[:, n_evict] - srt[:, n_evict - 1]) < 2e-3 * srt[:, n_evict]
+                near = int(tie.sum())
+                if uniform and tie[0]:
+                    acc = np.zeros(n, np.float32)
+                    for h in range(self.g.heads):                # the kernel's own summation order
+                        acc = acc + got[h, :n]
+                    feed = np.broadcast_to(acc.astype(np.float64), want.shape).copy()
+                elif not uniform:
+                    feed[tie] = got[tie][:, :n]
+            self.model.set_importance(feed)
+            self.near_tie_evictions = getattr(self, "near_tie_evictions", 0) + near
+        return want
 
     def step(self, q, qd, rows=None, g=None, og=None, scale=0.0, max_abs=OUT_MAX_ABS, mean_abs=OUT_MEAN_ABS,
              check_lse=False) -> StepResult:

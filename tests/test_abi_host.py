@@ -36,18 +36,28 @@ PAPER = dict(heads=12, head_dim=128, grid_h=48, grid_w=88, tile_h=8, tile_w=16, 
              radius_h=24, radius_w=24, topk=32)
 
 
+def up256(n):
+    return -(-n // 256) * 256
+
+
+def eviction_state_bytes(heads, groups, n_qb):
+    """visible-group -> slot table, importance per group, per-row scratch of the importance kernel"""
+    return up256(heads * groups * 4) + up256(heads * groups * 4) + up256(heads * n_qb * groups * 4)
+
+
 def test_cache_bytes_formula():
     g = B.Geom(**PAPER)
     nb = 6 * 6
     tiles = 12 * 6 * nb
     assert g.nb == nb
-    assert B.lcsa_cache_device_bytes(g) == 2 * tiles * 128 * 128 * 2 + tiles * 128 * 4
+    assert B.lcsa_cache_device_bytes(g) == 2 * tiles * 128 * 128 * 2 + tiles * 128 * 4 + eviction_state_bytes(12, 6, 72)
     tiny = B.Geom(1, 32, 6, 8, 4, 4, 2, 4, 4, 4, 4, dtype=B.LCSA_F32)
-    assert B.lcsa_cache_device_bytes(tiny) == 2 * (16 * 16 * 32 * 4) + 16 * 32 * 4
+    assert B.lcsa_cache_device_bytes(tiny) == 2 * (16 * 16 * 32 * 4) + 16 * 32 * 4 + eviction_state_bytes(1, 4, 8)
     # (2,8,8) blocks on the paper grid: 66 blocks per frame pair, 3 pairs in the ring, 128 tokens per block
     paper288 = B.Geom(**{**PAPER, "tile_w": 8, "tile_t": 2})
     assert paper288.nb == 66 and paper288.n_qb == 66
-    assert B.lcsa_cache_device_bytes(paper288) == 2 * (12 * 3 * 66) * 128 * 128 * 2 + (12 * 3 * 66) * 128 * 4
+    assert B.lcsa_cache_device_bytes(paper288) == 2 * (12 * 3 * 66) * 128 * 128 * 2 + (12 * 3 * 66) * 128 * 4 \
+        + eviction_state_bytes(12, 3, 66)
 
 
 @pytest.mark.parametrize("field,value", [
@@ -94,6 +104,22 @@ def test_host_side_validation_without_gpu():
     other = B.Geom(**{**PAPER, "grid_w": 80}).c()
     assert L.lcsa_select_blocks(ctypes.byref(other), fake, h, fake, fake, None, None) == -1
     assert L.lcsa_select_blocks(ctypes.byref(gc), None, h, fake, fake, None, None) == -1
+    # eviction policy: host-only switch, valid values only, importance needs a non-empty cache
+    assert L.lcsa_cache_eviction(h) == B.LCSA_EVICT_SLIDING and L.lcsa_cache_order_device(h) is None
+    assert L.lcsa_cache_set_eviction(h, 3) == -1 and L.lcsa_cache_set_eviction(h, -1) == -1
+    assert L.lcsa_cache_set_eviction(None, 1) == -1
+    assert L.lcsa_cache_set_eviction(h, B.LCSA_EVICT_IMPORTANCE_UNIFORM) == 0
+    assert L.lcsa_cache_eviction(h) == B.LCSA_EVICT_IMPORTANCE_UNIFORM and L.lcsa_cache_order_device(h) is not None
+    assert L.lcsa_cache_frame_slot(h, 0) == -1
+    assert L.lcsa_block_importance(ctypes.byref(gc), fake, h, 0.0, None) == -1      # nothing cached yet
+    assert L.lcsa_block_importance(ctypes.byref(gc), None, h, 0.0, None) == -1
+    assert L.lcsa_cache_set_eviction(h, B.LCSA_EVICT_SLIDING) == 0 and L.lcsa_cache_order_device(h) is None
+    # more than 64 groups of capacity: importance policies are not built for that
+    big = B.Geom(**{**PAPER, "grid_h": 8, "grid_w": 16, "cache_frames": 130}).c()
+    hb = ctypes.c_void_p()
+    assert L.lcsa_cache_init(ctypes.byref(hb), ctypes.byref(big), fake, 1 << 40) == 0
+    assert L.lcsa_cache_set_eviction(hb, B.LCSA_EVICT_IMPORTANCE_HEADWISE) == -2
+    L.lcsa_cache_free(hb)
     assert L.lcsa_cache_reset(h) == 0
     assert L.lcsa_cache_reset(None) == -1
     assert L.lcsa_cache_valid_frames(None) == -1

@@ -334,3 +334,65 @@ def test_temporal_blocks_reject_odd_frame_counts():
     with pytest.raises(B.LcsaError):
         B.lcsa_kv_cache_append(cache, k, k, 1)                       # one frame into two-frame blocks
     assert B.lcsa_cache_device_bytes(B.Geom(2, 128, 16, 16, 8, 8, 3, 6, 8, 8, 4, tile_t=2)) == 0   # q_frames not a multiple
+
+
+# ---- importance-based KV eviction (appendix on KV-cache eviction): head-wise and uniform ------------------
+
+def run_eviction_stream(w, policy, pattern, gains, **kw):
+    """Streams chunks through a cache with importance-based eviction on both sides: cache contents (per
+    head), selection, outputs and group importance are compared after every chunk.  Chunk c comes from one of
+    two unrelated static scenes (pattern[c]) with its keys scaled by gains[c], so that old frames of the
+    scene on screen outweigh newer frames of the other one.  Returns the pipeline."""
+    p = Pipeline(w, eviction=policy, **kw)
+    tol = dict(max_abs=F32_MAX, mean_abs=F32_MEAN) if w.dtype == "fp32" else {}
+    scenes = [wl.ChunkStream(w, 0), wl.ChunkStream(w, 1)]
+    for chunk, (scene, gain) in enumerate(zip(pattern, gains)):
+        q, k, v = scenes[scene].next()
+        k = k * np.float32(gain)
+        q, qd = p.feed(q, wl.round_to_bf16(k) if w.dtype == "bf16" else k, v)
+        p.check_pooled_k()
+        r = p.step(q, qd, **tol)
+        p.score_groups(q, qd)
+        say(f"{w.name} policy {policy} chunk {chunk}: groups per head {p.model.birth_order().tolist()}, "
+            f"max-abs {r.max_abs:.2e}")
+    say(f"{w.name} policy {policy}: {getattr(p, 'near_tie_evictions', 0)} eviction decisions were near-ties")
+    return p
+
+
+PATTERN = [0, 1, 0, 0, 1, 0, 1, 1, 0]
+GAINS = [1.0, 0.8, 0.95, 0.9, 0.85, 0.75, 1.0, 0.85, 0.9]      # at most 1: sharper softmax rows would raise |o| and with it the bf16 rounding of O
+
+
+@pytest.mark.parametrize("policy", [B.LCSA_EVICT_IMPORTANCE_HEADWISE, B.LCSA_EVICT_IMPORTANCE_UNIFORM])
+def test_importance_eviction_stream_matrix_core_path(policy):
+    w = wl.with_overrides(wl.WORKLOADS["small"], name="evict-small", heads=3, q_frames=1, cache_frames=4)
+    p = run_eviction_stream(w, policy, PATTERN, GAINS)
+    order = p.model.birth_order()
+    assert (order[:, -1] == 8).all()                                   # the chunk just appended is always there
+    assert (np.diff(order, axis=1) > 0).all()                          # temporal order is kept
+    assert not (order == np.arange(5, 9)).all(), "every decision equalled the sliding window: the test shows nothing"
+    if policy == B.LCSA_EVICT_IMPORTANCE_UNIFORM:
+        assert (order == order[0]).all()
+
+
+def test_importance_eviction_two_frame_groups_and_generic_path():
+    w = wl.with_overrides(wl.WORKLOADS["small"], name="evict-2x8x8", heads=2, tile_h=8, tile_w=8, cache_frames=8)
+    run_eviction_stream(w, B.LCSA_EVICT_IMPORTANCE_HEADWISE, PATTERN[:7], GAINS[:7], tile_t=2)
+    t = wl.with_overrides(wl.WORKLOADS["tiny"], name="evict-tiny", heads=2, grid_h=10, grid_w=14, q_frames=1, cache_frames=3,
+                          radius=4, topk=3)
+    run_eviction_stream(t, B.LCSA_EVICT_IMPORTANCE_UNIFORM, PATTERN, GAINS)
+
+
+def test_importance_scores_under_the_sliding_window_and_policy_rules():
+    """Scoring works under any policy (the sliding window ignores it); the policy can only change while the cache is empty."""
+    w = wl.with_overrides(wl.WORKLOADS["small"], name="score-small", heads=2)
+    p = Pipeline(w)
+    for _ in range(4):
+        q, qd = p.feed()
+    p.score_groups(q, qd)
+    p.check_pooled_k()
+    with pytest.raises(B.LcsaError):
+        B.lcsa_cache_set_eviction(p.cache, B.LCSA_EVICT_IMPORTANCE_HEADWISE)
+    B.lcsa_cache_reset(p.cache)
+    B.lcsa_cache_set_eviction(p.cache, B.LCSA_EVICT_IMPORTANCE_HEADWISE)
+    assert B.lcsa_cache_eviction(p.cache) == B.LCSA_EVICT_IMPORTANCE_HEADWISE
