@@ -89,16 +89,26 @@ def check_selection(sel_idx, sel_cnt, o_idx, o_cnt, o_gap, og, kv_frames):
 
 
 def check_outputs(o_gpu: torch.Tensor, q, K, V, og, kv_frames, sel_idx, sel_cnt, rows, scale=0.0,
-                  max_abs=OUT_MAX_ABS, mean_abs=OUT_MEAN_ABS):
+                  max_abs=OUT_MAX_ABS, mean_abs=OUT_MEAN_ABS, bf16_relative=False):
     """Compares against the oracle's attention on the SAME selection (the GPU's, which equals the
-    oracle's except on reported near-tie rows)."""
+    oracle's except on reported near-tie rows).
+
+    bf16_relative: for shapes where a row attends to a handful of keys (tiny clipped blocks) |o| reaches
+    4 and more and the rounding of O to bf16 alone (half an ulp = up to 2^-8 |o|) exceeds max_abs; the
+    bound is then 2^-8 |o| + 2e-3 per element (rounding of the result + everything inside the kernel)."""
     want = oracle.attend(q, K, V, og, kv_frames, sel_idx, sel_cnt, scale=scale, rows=rows)
     got = o_gpu.float().cpu().numpy().astype(np.float64)
     done = ~np.isnan(want)
     assert done.any()
     err = np.abs(got - want)[done]
     assert np.isfinite(got[done]).all()
-    assert err.max() <= max_abs, f"max-abs {err.max():.3e} > {max_abs}"
+    if bf16_relative:
+        bound = 2.0 ** -8 * np.abs(want[done]) + 2e-3
+        worst = int(np.argmax(err - bound))
+        assert (err <= bound).all(), f"error {err[worst]:.3e} at |o| = {abs(want[done][worst]):.3f} exceeds {bound[worst]:.3e}"
+        return float(err.max()), float(err.mean())
+    worst = int(np.argmax(err))
+    assert err.max() <= max_abs, f"max-abs {err.max():.3e} > {max_abs} (at |o| = {abs(want[done][worst]):.3f})"
     assert err.mean() <= mean_abs, f"mean-abs {err.mean():.3e} > {mean_abs}"
     return float(err.max()), float(err.mean())
 
@@ -187,7 +197,7 @@ class Pipeline:
         return want
 
     def step(self, q, qd, rows=None, g=None, og=None, scale=0.0, max_abs=OUT_MAX_ABS, mean_abs=OUT_MEAN_ABS,
-             check_lse=False) -> StepResult:
+             check_lse=False, bf16_relative=False) -> StepResult:
         """pool -> select -> attend on the GPU, the same on the oracle, compare."""
         g = g or self.g
         og = og or self.og
@@ -207,7 +217,7 @@ class Pipeline:
         fin = np.isfinite(o_gap)
         assert (np.isinf(ggap) == ~fin).all()
         np.testing.assert_allclose(ggap[fin], o_gap[fin], rtol=0, atol=1e-3)
-        mx, mean = check_outputs(o, q, K, V, og, kvf, s_idx, s_cnt, rows, scale, max_abs, mean_abs)
+        mx, mean = check_outputs(o, q, K, V, og, kvf, s_idx, s_cnt, rows, scale, max_abs, mean_abs, bf16_relative)
         if check_lse:
             _, want_lse = oracle.attend(q, K, V, og, kvf, s_idx, s_cnt, scale=scale, rows=rows, with_lse=True)
             done = ~np.isnan(want_lse)

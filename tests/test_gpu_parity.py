@@ -396,3 +396,39 @@ def test_importance_scores_under_the_sliding_window_and_policy_rules():
     B.lcsa_cache_reset(p.cache)
     B.lcsa_cache_set_eviction(p.cache, B.LCSA_EVICT_IMPORTANCE_HEADWISE)
     assert B.lcsa_cache_eviction(p.cache) == B.LCSA_EVICT_IMPORTANCE_HEADWISE
+
+
+# ---- seeded sweep over geometries: block shapes, ragged grids, windows, top-k, cache lengths --------------
+
+def _sweep_cases():
+    rng = np.random.default_rng(20251012)
+    shapes = [(1, 8, 16), (1, 16, 8), (2, 8, 8), (1, 4, 32), (4, 4, 8), (2, 4, 16), (1, 2, 64), (8, 4, 4)]
+    cases = []
+    for i in range(16):
+        tt, th, tw = shapes[i % len(shapes)]
+        q_groups = int(rng.integers(1, 3))
+        cap_groups = q_groups + int(rng.integers(0, 4))
+        cases.append(dict(
+            tile_t=tt, tile_h=th, tile_w=tw, heads=int(rng.integers(1, 4)),
+            grid_h=int(rng.integers(th, 5 * th + 1)), grid_w=int(rng.integers(tw, 4 * tw + 1)),
+            q_frames=q_groups * tt, cache_frames=cap_groups * tt,
+            radius=(int(rng.choice([-1, 0, th, 2 * th + 3])), int(rng.choice([-1, 0, tw, 2 * tw + 5]))),
+            topk=int(rng.integers(1, 40)), window_mode=int(rng.integers(0, 2)), n_chunks=int(rng.integers(1, 6))))
+    return cases
+
+
+@pytest.mark.parametrize("case", _sweep_cases(), ids=lambda c: f"{c['tile_t']}x{c['tile_h']}x{c['tile_w']}-{c['grid_h']}x{c['grid_w']}-k{c['topk']}")
+def test_geometry_sweep_matrix_core_path(case):
+    """128-token blocks of eight shapes on grids they do not divide, 1-3 heads (odd numbers of work items leave
+    half a workgroup idle), per-axis radii incl. 0 and unbounded, both boundary rules, top-k below and above the
+    number of admissible blocks, caches that are not yet full; every row is compared with the oracle."""
+    w = wl.with_overrides(wl.WORKLOADS["small"], name="sweep", heads=case["heads"], grid_h=case["grid_h"], grid_w=case["grid_w"],
+                          tile_h=case["tile_h"], tile_w=case["tile_w"], q_frames=case["q_frames"],
+                          cache_frames=case["cache_frames"], topk=case["topk"])
+    p = Pipeline(w, tile_t=case["tile_t"], radius=case["radius"], window_mode=case["window_mode"])
+    assert p.cache is not None and p.g.tile_t * p.g.tile_h * p.g.tile_w == 128
+    for _ in range(case["n_chunks"]):
+        q, qd = p.feed()
+    p.check_pooled_k()
+    r = p.step(q, qd, check_lse=True, bf16_relative=True)
+    say(f"sweep {case}: rows {r.rows_checked}, near-ties {r.near_tie_rows}, max-abs {r.max_abs:.2e}")
