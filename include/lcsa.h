@@ -182,7 +182,9 @@ int32_t lcsa_select_blocks(const lcsa_geom *geom, const float *pooled_q, const l
  * log of the softmax denominator.  scale <= 0 selects 1/sqrt(head_dim).  Products are
  * formed from the stored element type with float accumulation and a float online
  * softmax; on the matrix-core path probabilities and V enter the second product as IEEE half.
- * Rows with sel_cnt = 0 produce zeros (lse = -inf).
+ * Rows with sel_cnt = 0 produce zeros (lse = -inf).  Counts outside [0, topk] and ids outside the
+ * visible blocks are clamped into range by the kernels (the row's result is then meaningless, but
+ * nothing outside the cache is read).
  */
 int32_t lcsa_sparse_attn_fwd(const lcsa_geom *geom,
                              const void *q, int64_t q_stride_tok, int64_t q_stride_head,

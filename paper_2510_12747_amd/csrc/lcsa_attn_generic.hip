@@ -64,7 +64,7 @@ __global__ __launch_bounds__(64 * kWaves) void attn_generic_kernel(
     const int fq = qb / g.nb, tile = qb - fq * g.nb, by = tile / g.tx, bx = tile - by * g.tx;
     const int qvh = min(g.th, g.H - by * g.th), qvw = min(g.tw, g.W - bx * g.tw);
     const int64_t row = (int64_t)head * n_qb + qb;
-    const int cnt = sel_cnt[row];
+    const int cnt = min(max(sel_cnt[row], 0), g.topk);       // a row holds at most topk ids
     const int32_t *sel = sel_idx + row * g.topk;
     const T *kc = (const T *)c.k, *vc = (const T *)c.v;
 
@@ -81,7 +81,7 @@ __global__ __launch_bounds__(64 * kWaves) void attn_generic_kernel(
         __syncthreads();
         float m = -__builtin_inff(), l = 0.f, acc[DPL] = {0.f, 0.f, 0.f, 0.f};
         for (int b = 0; b < cnt; ++b) {
-            const int kb = sel[b];
+            const int kb = min(max(sel[b], 0), c.valid * g.nb - 1);   // ids outside the cache must not become wild addresses
             const int f = kb / g.nb, kt = kb - f * g.nb, kby = kt / g.tx, kbx = kt - kby * g.tx;
             const int vh = min(g.th, g.H - kby * g.th), vw = min(g.tw, g.W - kbx * g.tw);
             const int slot = cache_slot(c, g, head, f);

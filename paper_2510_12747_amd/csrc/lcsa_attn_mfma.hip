@@ -110,6 +110,7 @@ __device__ inline float block_row_max(const f32x16 (&sc)[4], int nf) {
 // A selected key block as the loop wants it: ring-slot tile index and its number of valid keys.
 //   bits 0..23 tile index (slot*nb + tile), bits 24..30 valid keys - 1
 __device__ inline uint32_t pack_block(const KGeom &g, const KCache &c, int head, int kb, int ph, int pw) {
+    kb = min(max(kb, 0), c.valid * g.nb - 1);          // ids outside the cache (corrupt input) must not become wild addresses
     const int f = kb / g.nb, kt = kb - f * g.nb;
     const int kby = kt / g.tx, kbx = kt - kby * g.tx;
     const int vh = kby == g.ty - 1 ? ph : g.th, vw = kbx == g.tx - 1 ? pw : g.tw;
@@ -176,8 +177,8 @@ __global__ __launch_bounds__(512, 2) void attn_mfma_kernel(
         for (int s = 0; s < 8; ++s) bq[s] = *(const bf16x8 *)(qp + s * 16);
     }
 
-    cnt = __builtin_amdgcn_readfirstlane(cnt);
-    other_cnt = __builtin_amdgcn_readfirstlane(other_cnt);
+    cnt = min(max(__builtin_amdgcn_readfirstlane(cnt), 0), g.topk);            // a row holds at most topk ids
+    other_cnt = min(max(__builtin_amdgcn_readfirstlane(other_cnt), 0), g.topk);
     const int n_iter = max(cnt, other_cnt);
     const int64_t row = (int64_t)head * n_qb + qb;
     const int32_t *sel = sel_idx + row * g.topk;

@@ -47,8 +47,8 @@ def test_small_video_all_rows():
 def test_paper_scale_sampled_rows():
     w = wl.WORKLOADS["paper"]
     _, og = geoms(w)
-    say("paper: full selection check, outputs on sampled rows, layers 0 and 7")
-    for layer in (0, 7):
+    say("paper: full selection check, outputs on sampled rows, first and last layer call of the benchmark step")
+    for layer in (0, 29):
         run_primed(w, layer, rows=sample_rows(og, 48, seed=layer))
 
 
@@ -396,6 +396,31 @@ def test_importance_scores_under_the_sliding_window_and_policy_rules():
     B.lcsa_cache_reset(p.cache)
     B.lcsa_cache_set_eviction(p.cache, B.LCSA_EVICT_IMPORTANCE_HEADWISE)
     assert B.lcsa_cache_eviction(p.cache) == B.LCSA_EVICT_IMPORTANCE_HEADWISE
+
+
+def test_out_of_range_selection_input_is_clamped():
+    """Counts beyond top-k or below zero and ids outside the visible blocks (a caller's bug) are clamped by the
+    kernels: such rows give meaningless but finite results and nothing outside the cache is touched; rows with
+    sane input are unaffected."""
+    for w in (wl.with_overrides(wl.WORKLOADS["small"], name="clamp-small", heads=2),
+              wl.with_overrides(wl.WORKLOADS["tiny"], name="clamp-tiny", heads=2)):
+        p = Pipeline(w)
+        for _ in range(3):
+            q, qd = p.feed()
+        pq = B.lcsa_pool_blocks(p.g, qd, p.g.q_frames)
+        sel_idx, sel_cnt, _ = B.lcsa_select_blocks(p.g, pq, p.cache)
+        good = B.lcsa_sparse_attn_fwd(p.g, qd, p.cache, sel_idx, sel_cnt).float().cpu()
+        bad_idx, bad_cnt = sel_idx.clone(), sel_cnt.clone()
+        bad_idx[0, 0, :] = 1 << 30
+        bad_idx[0, 1, 0] = -7
+        bad_cnt[0, 2] = p.g.topk + 1000
+        bad_cnt[0, 3] = -3
+        out = B.lcsa_sparse_attn_fwd(p.g, qd, p.cache, bad_idx, bad_cnt).float().cpu()
+        torch.cuda.synchronize()
+        assert torch.isfinite(out).all()
+        np.testing.assert_array_equal(out[:, 1].numpy(), good[:, 1].numpy())           # the untouched head
+        assert (out[:, 0] != good[:, 0]).any()
+        say(f"{w.name}: corrupt rows gave finite output")
 
 
 # ---- seeded sweep over geometries: block shapes, ragged grids, windows, top-k, cache lengths --------------
