@@ -262,7 +262,9 @@ def main() -> int:
                      "traffic": ATTN_TRAFFIC_BYTES.get((args.workload, topk)) if not (args.blocks or args.grid or args.cache_frames) and args.radius is None and policy == B.LCSA_EVICT_SLIDING else None,
                      "flop_per_launch_useful": useful_flop, "flop_per_launch_issued": issued_flop,
                      "issued_tflops": round(issued_flop / (attn_avg_ms * 1e-3) / 1e12, 2),
-                     "avg_launch_ms": round(attn_avg_ms, 5), "min_launch_ms": round(float(attn_ms.min()), 5)},
+                     "avg_launch_ms": round(attn_avg_ms, 5), "min_launch_ms": round(float(attn_ms.min()), 5),
+                     # beside the nominal peak: the same figure against what a register-only MFMA loop sustains here
+                     "frac_of_measured_mfma_loop": round(achieved / probe_tflops, 4)},
         "setup_s": round(setup_s, 1),
     }
 
