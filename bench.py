@@ -29,7 +29,7 @@ PEAK_HBM_GBS = 8000.0
 # HBM-side bytes per attention launch (L2 <-> fabric), from the rocprofv3 --pmc passes summarised in
 # profiles/hot_path_paper_scale_pmc.txt: FETCH_SIZE x 2.0 (factor from a 1 GiB copy) + WRITE_SIZE x 1.0, in bytes.
 # Counters cannot be read from inside this script; the figure is only quoted for the workload it was taken on.
-ATTN_TRAFFIC_BYTES = {("paper", 32): 279.3e6 + 25.9e6}
+ATTN_TRAFFIC_BYTES = {("paper", 32): 278.9e6 + 25.9e6}
 
 WORKLOAD_TEXT = {
     "paper": "paper-scale 768x1408: 48x88 tokens/frame, 2 query + 4 cached frames, 8x16 tiles, radius 24, top-k 32, 30 layer calls",
