@@ -173,7 +173,10 @@ class Cache:
 
     def __del__(self):
         if getattr(self, "handle", None):
-            lib().lcsa_cache_free(self.handle)
+            try:
+                lib().lcsa_cache_free(self.handle)
+            except Exception:      # interpreter shutdown: the module globals may already be gone
+                pass
             self.handle = None
 
 
