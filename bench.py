@@ -53,6 +53,10 @@ def main() -> int:
     ap.add_argument("--cache-frames", type=int, default=0, help="override the sliding-window capacity in frames")
     ap.add_argument("--eviction", default="sliding", choices=["sliding", "headwise", "uniform"],
                     help="KV-cache eviction: the paper's default sliding window, or importance-based (adds lcsa_block_importance to every layer call)")
+    ap.add_argument("--graph", action="store_true",
+                    help="replay the layer calls of a step from captured HIP graphs; needs the device-side slot table of an "
+                         "importance policy: with --eviction sliding the head-wise policy runs unscored, which evicts the oldest "
+                         "frames exactly like the sliding window")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device-to-device copy (reference point for HBM byte counters)")
@@ -88,6 +92,9 @@ def main() -> int:
     n_qb = g.n_qb
     policy = {"sliding": B.LCSA_EVICT_SLIDING, "headwise": B.LCSA_EVICT_IMPORTANCE_HEADWISE,
               "uniform": B.LCSA_EVICT_IMPORTANCE_UNIFORM}[args.eviction]
+    scoring = policy != B.LCSA_EVICT_SLIDING
+    if args.graph and not scoring:
+        policy = B.LCSA_EVICT_IMPORTANCE_HEADWISE       # unscored: oldest first, with the ring position kept on the device
 
     def dev(x):
         return torch.from_numpy(wl.bf16_bits(x).view(np.int16)).view(torch.bfloat16).cuda()
@@ -135,7 +142,7 @@ def main() -> int:
         B.lcsa_sparse_attn_fwd(g, q, L["cache"], L["sel_idx"], L["sel_cnt"], L["o"])
         if attn_ev: attn_ev[1].record()
         if ev: ev[3].record()
-        if policy != B.LCSA_EVICT_SLIDING:
+        if scoring:
             B.lcsa_block_importance(g, L["pq"], L["cache"])     # scores the visible groups for the next append
         if ev: ev[5].record()
 
@@ -155,16 +162,30 @@ def main() -> int:
     # (all launches go to torch's current stream, which is the stream these events are recorded on)
     attn_ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in layers]
                for _ in range(args.steps)]
+    graphs = []
+    if args.graph:
+        # one graph per position of the chunk rotation: the inputs of a captured call are fixed
+        for _ in range(len(layers[0]["chunks"])):
+            gph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(gph):
+                for L in layers:
+                    layer_call(L)
+            graphs.append(gph)
+        for s_ in range(args.warmup):
+            graphs[s_ % len(graphs)].replay()
     torch.cuda.synchronize()
     t_start = time.perf_counter()
     for s in range(args.steps):
-        for L, (e0, e1) in zip(layers, attn_ev[s]):
-            layer_call(L, attn_ev=(e0, e1))
+        if args.graph:
+            graphs[(args.warmup + s) % len(graphs)].replay()
+        else:
+            for L, (e0, e1) in zip(layers, attn_ev[s]):
+                layer_call(L, attn_ev=(e0, e1))
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t_start
     ms_per_step = elapsed * 1e3 / args.steps
     ms_per_layer = ms_per_step / n_layers
-    attn_ms = np.array([[e0.elapsed_time(e1) for (e0, e1) in step] for step in attn_ev])
+    attn_ms = None if args.graph else np.array([[e0.elapsed_time(e1) for (e0, e1) in step] for step in attn_ev])
 
     # ---- untimed breakdown pass: events between the four calls ------------------------------------
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in layers]
@@ -174,6 +195,8 @@ def main() -> int:
     torch.cuda.synchronize()
     brk = np.array([[e[4].elapsed_time(e[0]), e[0].elapsed_time(e[1]), e[1].elapsed_time(e[2]), e[2].elapsed_time(e[3]),
                      e[3].elapsed_time(e[5])] for e in ev]).mean(axis=0)
+    if attn_ms is None:      # launches inside a graph carry no events: the attention launches of this eager pass stand in
+        attn_ms = np.array([[e[2].elapsed_time(e[3]) for e in ev]])
 
     # ---- what this chip sustains on trivial loops, quoted beside the nominal peaks (outside the timed region):
     # back-to-back bf16 matrix instructions on registers, and a 1 GiB device-to-device copy
@@ -245,11 +268,11 @@ def main() -> int:
                    "layers_per_step": n_layers, "q_tokens": tok_new, "kv_tokens": w.cache_frames * w.tokens_per_frame,
                    "block_shape": [tile_t, w.tile_h, w.tile_w], "blocks_per_group": g.nb, "query_blocks": n_qb,
                    "grid": [w.grid_h, w.grid_w], "cache_frames": w.cache_frames, "topk": topk, "radius": radius,
-                   "eviction": args.eviction},
+                   "eviction": args.eviction, "launch": "hip graphs" if args.graph else "eager"},
         "effective_tflops_whole_path": round(useful_flop / (ms_per_layer * 1e-3) / 1e12, 2),
         "kernel_ms_per_layer": {"kv_cache_append": round(float(brk[0]), 5), "pool_blocks": round(float(brk[1]), 5),
                                 "select_blocks": round(float(brk[2]), 5), "sparse_attn_fwd": round(attn_avg_ms, 5),
-                                **({"block_importance": round(float(brk[4]), 5)} if policy != B.LCSA_EVICT_SLIDING else {})},
+                                **({"block_importance": round(float(brk[4]), 5)} if scoring else {})},
         "hbm_gbs": {"kv_cache_append": round(append_bytes / (brk[0] * 1e-3) / 1e9, 1),
                     "pool_blocks": round(pool_bytes / (brk[1] * 1e-3) / 1e9, 1),
                     "select_blocks": round(select_bytes / (brk[2] * 1e-3) / 1e9, 1)},

@@ -457,3 +457,58 @@ def test_geometry_sweep_matrix_core_path(case):
     p.check_pooled_k()
     r = p.step(q, qd, check_lse=True, bf16_relative=True)
     say(f"sweep {case}: rows {r.rows_checked}, near-ties {r.near_tie_rows}, max-abs {r.max_abs:.2e}")
+
+
+# ---- the streaming path inside a captured HIP graph -----------------------------------------------------
+
+def test_streaming_layer_call_replays_from_a_captured_graph():
+    """Under an importance policy the visible-group -> slot table lives on the device, and once the cache is full
+    every layer call has the same arguments: one captured graph of (evict + append, pool, select, attend) can be
+    replayed chunk after chunk.  Unscored, the policy evicts the oldest group, i.e. it is the sliding window.
+    Every replay is compared bit for bit with the same call made eagerly on a twin cache, with eager work and
+    synchronisations between the replays, and with the oracle's sliding-window model."""
+    w = wl.with_overrides(wl.WORKLOADS["small"], name="graph-small", heads=2, q_frames=1, cache_frames=4)
+    g, og = geoms(w)
+    stream = wl.ChunkStream(w, 0)
+    chunks = [stream.next() for _ in range(9)]
+    model = oracle.SlidingWindowCache(w.cache_frames)
+    caches = [B.lcsa_cache_init(g), B.lcsa_cache_init(g)]
+    for c in caches:
+        B.lcsa_cache_set_eviction(c, B.LCSA_EVICT_IMPORTANCE_HEADWISE)
+    for q, k, v in chunks[:4]:                                  # fill both caches eagerly
+        model.append(k, v, 1)
+        for c in caches:
+            B.lcsa_kv_cache_append(c, to_device(k, "bf16"), to_device(v, "bf16"), 1)
+    qs, ks, vs = (torch.empty_like(to_device(x, "bf16")) for x in chunks[0])
+    outs = [dict(pq=torch.empty(g.heads, g.n_qb, g.head_dim, dtype=torch.float32, device="cuda"),
+                 si=torch.empty(g.heads, g.n_qb, g.topk, dtype=torch.int32, device="cuda"),
+                 sc=torch.empty(g.heads, g.n_qb, dtype=torch.int32, device="cuda"),
+                 o=torch.empty_like(qs)) for _ in caches]
+
+    def layer_call(cache, out):
+        B.lcsa_kv_cache_append(cache, ks, vs, 1)
+        B.lcsa_pool_blocks(g, qs, 1, out["pq"])
+        B.lcsa_select_blocks(g, out["pq"], cache, out["si"], out["sc"], want_gap=False)
+        B.lcsa_sparse_attn_fwd(g, qs, cache, out["si"], out["sc"], out["o"])
+
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        layer_call(caches[1], outs[1])                          # recorded, not run
+    for n, (q, k, v) in enumerate(chunks[4:]):
+        say(f"graph replay {n}")
+        for dst, src in ((qs, q), (ks, k), (vs, v)):
+            dst.copy_(to_device(src, "bf16"))
+        model.append(k, v, 1)
+        layer_call(caches[0], outs[0])                          # eager twin
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for key in ("si", "sc", "o", "pq"):
+            assert torch.equal(outs[0][key], outs[1][key]), f"replay {n}: {key} differs from the eager call"
+        assert torch.equal(B.lcsa_cache_order(caches[0]), B.lcsa_cache_order(caches[1]))
+        K, V = model.visible()
+        S = oracle.scores(oracle.pool(q, og, 1), oracle.pool(K, og, 4))
+        o_idx, o_cnt, o_gap = oracle.select(S, og, 4)
+        s_idx, s_cnt, _, _ = check_selection(outs[1]["si"], outs[1]["sc"], o_idx, o_cnt, o_gap, og, 4)
+        check_outputs(outs[1]["o"], q, K, V, og, 4, s_idx, s_cnt, None)
