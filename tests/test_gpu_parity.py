@@ -78,6 +78,21 @@ def test_4k_streaming_ring_and_topk_sweep():
         say(f"4k top-k {k}: near-tie rows {r.near_tie_rows}, differs {r.sel_mismatch_rows}, max-abs {r.max_abs:.2e}")
 
 
+def test_full_sizes_every_row():
+    """At full size the other tests sample rows; here every output row of one paper-scale layer call and of one
+    4K chunk (ring full) goes through the oracle: 864 + 3060 work items, each placed on a workgroup, a group
+    and an XCD by the launch arithmetic that the benchmark uses."""
+    p, r = run_primed(wl.WORKLOADS["paper"], layer=3)
+    assert r.rows_checked == 12 * 72
+    w = wl.WORKLOADS["4k"]
+    p = Pipeline(w)
+    for _ in range(6):
+        q, qd = p.feed()
+    r = p.step(q, qd)
+    assert r.rows_checked == 12 * 255
+    say(f"4k all rows: near-tie rows {r.near_tie_rows}, differs {r.sel_mismatch_rows}, max-abs {r.max_abs:.2e}, mean-abs {r.mean_abs:.2e}")
+
+
 # ---- edge cases and variants -------------------------------------------------------------------
 
 SMALL_MFMA = wl.with_overrides(wl.WORKLOADS["small"], name="edge", heads=3, grid_h=20, grid_w=40, radius=16, topk=6)
