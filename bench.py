@@ -57,6 +57,8 @@ def main() -> int:
                     help="replay the layer calls of a step from captured HIP graphs; needs the device-side slot table of an "
                          "importance policy: with --eviction sliding the head-wise policy runs unscored, which evicts the oldest "
                          "frames exactly like the sliding window")
+    ap.add_argument("--two-calls", action="store_true",
+                    help="pool and select with lcsa_pool_blocks + lcsa_select_blocks instead of the fused lcsa_pool_select_blocks")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device-to-device copy (reference point for HBM byte counters)")
@@ -134,9 +136,13 @@ def main() -> int:
         L["turn"] += 1
         B.lcsa_kv_cache_append(L["cache"], k, v, w.q_frames)
         if ev: ev[0].record()
-        B.lcsa_pool_blocks(g, q, w.q_frames, L["pq"])
-        if ev: ev[1].record()
-        B.lcsa_select_blocks(g, L["pq"], L["cache"], L["sel_idx"], L["sel_cnt"], want_gap=False)
+        if args.two_calls:
+            B.lcsa_pool_blocks(g, q, w.q_frames, L["pq"])
+            if ev: ev[1].record()
+            B.lcsa_select_blocks(g, L["pq"], L["cache"], L["sel_idx"], L["sel_cnt"], want_gap=False)
+        else:
+            if ev: ev[1].record()
+            B.lcsa_pool_select_blocks(g, q, L["cache"], L["pq"], L["sel_idx"], L["sel_cnt"], want_gap=False)
         if ev: ev[2].record()
         if attn_ev: attn_ev[0].record()
         B.lcsa_sparse_attn_fwd(g, q, L["cache"], L["sel_idx"], L["sel_cnt"], L["o"])
@@ -270,12 +276,15 @@ def main() -> int:
                    "grid": [w.grid_h, w.grid_w], "cache_frames": w.cache_frames, "topk": topk, "radius": radius,
                    "eviction": args.eviction, "launch": "hip graphs" if args.graph else "eager"},
         "effective_tflops_whole_path": round(useful_flop / (ms_per_layer * 1e-3) / 1e12, 2),
-        "kernel_ms_per_layer": {"kv_cache_append": round(float(brk[0]), 5), "pool_blocks": round(float(brk[1]), 5),
-                                "select_blocks": round(float(brk[2]), 5), "sparse_attn_fwd": round(attn_avg_ms, 5),
+        "kernel_ms_per_layer": {"kv_cache_append": round(float(brk[0]), 5),
+                                **({"pool_blocks": round(float(brk[1]), 5), "select_blocks": round(float(brk[2]), 5)}
+                                   if args.two_calls else {"pool_select_blocks": round(float(brk[2]), 5)}),
+                                "sparse_attn_fwd": round(attn_avg_ms, 5),
                                 **({"block_importance": round(float(brk[4]), 5)} if scoring else {})},
         "hbm_gbs": {"kv_cache_append": round(append_bytes / (brk[0] * 1e-3) / 1e9, 1),
-                    "pool_blocks": round(pool_bytes / (brk[1] * 1e-3) / 1e9, 1),
-                    "select_blocks": round(select_bytes / (brk[2] * 1e-3) / 1e9, 1)},
+                    **({"pool_blocks": round(pool_bytes / (brk[1] * 1e-3) / 1e9, 1),
+                        "select_blocks": round(select_bytes / (brk[2] * 1e-3) / 1e9, 1)} if args.two_calls else
+                       {"pool_select_blocks": round((pool_bytes + select_bytes) / (brk[2] * 1e-3) / 1e9, 1)})},
         "device": {"name": prop.name, "compute_units": n_cu,
                    "nominal_peak_tflops": PEAK_BF16_TFLOPS, "nominal_hbm_gbs": 8000.0},
         "measured_peaks": {"mfma_bf16_register_loop_tflops": round(probe_tflops, 1),

@@ -172,6 +172,17 @@ int32_t lcsa_pool_blocks(const lcsa_geom *geom, const void *x,
 int32_t lcsa_select_blocks(const lcsa_geom *geom, const float *pooled_q, const lcsa_cache *cache,
                            int32_t *sel_idx, int32_t *sel_cnt, float *gap, void *stream);
 
+/*
+ * lcsa_pool_blocks and lcsa_select_blocks in one launch, for the chunk's queries (q: device,
+ * geom->dtype, raster order over q_frames frames): every workgroup pools its own query block, with
+ * the arithmetic of lcsa_pool_blocks (pooled_q, device float [heads][n_qb][head_dim], receives the
+ * same values, bit for bit), then selects.  Saves one launch and the round trip of the pooled queries.
+ * Arguments, limits and results otherwise as for the two calls.
+ */
+int32_t lcsa_pool_select_blocks(const lcsa_geom *geom, const void *q, int64_t q_stride_tok, int64_t q_stride_head,
+                                const lcsa_cache *cache, float *pooled_q,
+                                int32_t *sel_idx, int32_t *sel_cnt, float *gap, void *stream);
+
 /* ---- block-sparse attention (Sec. 3.2: full attention on the kept pairs; eq. 1) --------------- */
 
 /*

@@ -99,6 +99,7 @@ def lib():
         L.lcsa_select_blocks.argtypes = [_gp, _vp, _vp, _vp, _vp, _vp, _vp]
         L.lcsa_sparse_attn_fwd.argtypes = [_gp, _vp, _i64, _i64, _vp, _vp, _vp, _vp, _i64, _i64, _vp, _f32, _vp]
         L.lcsa_probe_mfma_bf16.argtypes = [_vp, _i32, _i32, _vp]
+        L.lcsa_pool_select_blocks.argtypes = [_gp, _vp, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _vp]
         L.lcsa_cache_set_eviction.argtypes = [_vp, _i32]
         L.lcsa_cache_eviction.argtypes = [_vp]
         L.lcsa_block_importance.argtypes = [_gp, _vp, _vp, _f32, _vp]
@@ -111,7 +112,7 @@ def lib():
         L.lcsa_last_hip_error.restype = ctypes.c_char_p
         for f in ("lcsa_cache_init", "lcsa_cache_reset", "lcsa_cache_valid_frames", "lcsa_cache_frame_slot",
                   "lcsa_kv_cache_append", "lcsa_pool_blocks", "lcsa_select_blocks", "lcsa_sparse_attn_fwd",
-                  "lcsa_probe_mfma_bf16", "lcsa_cache_set_eviction", "lcsa_cache_eviction", "lcsa_block_importance"):
+                  "lcsa_probe_mfma_bf16", "lcsa_pool_select_blocks", "lcsa_cache_set_eviction", "lcsa_cache_eviction", "lcsa_block_importance"):
             getattr(L, f).restype = _i32
         _lib = L
     return _lib
@@ -286,6 +287,32 @@ def lcsa_select_blocks(geom: Geom, pooled_q: torch.Tensor, cache: Cache, sel_idx
                                     sel_cnt.data_ptr(), gap.data_ptr() if gap is not None else None,
                                     _stream(stream)), "lcsa_select_blocks")
     return sel_idx, sel_cnt, gap
+
+
+def lcsa_pool_select_blocks(geom: Geom, q: torch.Tensor, cache: Cache, pooled_q=None, sel_idx=None, sel_cnt=None, gap=None,
+                            want_gap: bool = True, stream=None):
+    """lcsa_pool_blocks + lcsa_select_blocks in one launch; returns (pooled_q, sel_idx, sel_cnt, gap)."""
+    n_qb = geom.n_qb
+    qp, qst, qsh = _tok(q)
+    if q.dtype != geom.torch_dtype or q.shape != (geom.q_frames * geom.tokens_per_frame, geom.heads, geom.head_dim):
+        raise LcsaError("lcsa_pool_select_blocks: q shape/dtype mismatch")
+    dev = q.device
+    if pooled_q is None:
+        pooled_q = torch.empty(geom.heads, n_qb, geom.head_dim, dtype=torch.float32, device=dev)
+    if sel_idx is None:
+        sel_idx = torch.empty(geom.heads, n_qb, geom.topk, dtype=torch.int32, device=dev)
+    if sel_cnt is None:
+        sel_cnt = torch.empty(geom.heads, n_qb, dtype=torch.int32, device=dev)
+    if gap is None and want_gap:
+        gap = torch.empty(geom.heads, n_qb, dtype=torch.float32, device=dev)
+    assert pooled_q.is_contiguous() and pooled_q.dtype == torch.float32 and pooled_q.numel() == geom.heads * n_qb * geom.head_dim
+    assert sel_idx.is_contiguous() and sel_cnt.is_contiguous() and sel_idx.dtype == torch.int32 and sel_cnt.dtype == torch.int32
+    assert sel_idx.numel() == geom.heads * n_qb * geom.topk and sel_cnt.numel() == geom.heads * n_qb
+    g = geom.c()
+    _check(lib().lcsa_pool_select_blocks(ctypes.byref(g), qp, qst, qsh, cache.handle, pooled_q.data_ptr(), sel_idx.data_ptr(),
+                                         sel_cnt.data_ptr(), gap.data_ptr() if gap is not None else None,
+                                         _stream(stream)), "lcsa_pool_select_blocks")
+    return pooled_q, sel_idx, sel_cnt, gap
 
 
 def lcsa_sparse_attn_fwd(geom: Geom, q: torch.Tensor, cache: Cache, sel_idx: torch.Tensor, sel_cnt: torch.Tensor,

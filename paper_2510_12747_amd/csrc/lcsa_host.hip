@@ -225,6 +225,21 @@ int32_t lcsa_select_blocks(const lcsa_geom *geom, const float *pooled_q, const l
     return hip_status(launch_select(kg, cache->kc, pooled_q, sel_idx, sel_cnt, gap, mc, (hipStream_t)stream));
 }
 
+int32_t lcsa_pool_select_blocks(const lcsa_geom *geom, const void *q, int64_t q_stride_tok, int64_t q_stride_head,
+                                const lcsa_cache *cache, float *pooled_q, int32_t *sel_idx, int32_t *sel_cnt, float *gap,
+                                void *stream) {
+    if (!geom_ok(geom) || !cache || !pooled_q || !sel_idx || !sel_cnt) return LCSA_EINVAL;
+    if (!same_geom(geom, cache->geom)) return LCSA_EINVAL;
+    if (cache->kc.valid * geom->tile_t < geom->q_frames) return LCSA_EINVAL;
+    KGeom kg = derive(*geom);
+    if (!tensor_ok(q, q_stride_tok, q_stride_head, kg)) return LCSA_EINVAL;
+    if ((int64_t)geom->q_frames * kg.H * kg.W > (1ll << 30)) return LCSA_EINVAL;
+    const int mc = max_candidates(kg, cache->kc.valid);
+    if (mc > 8192) return LCSA_EUNSUPPORTED;
+    return hip_status(launch_pool_select(kg, cache->kc, q, q_stride_tok, q_stride_head, pooled_q, sel_idx, sel_cnt, gap, mc,
+                                         (hipStream_t)stream));
+}
+
 int32_t lcsa_block_importance(const lcsa_geom *geom, const float *pooled_q, lcsa_cache *cache, float scale, void *stream) {
     if (!geom_ok(geom) || !cache || !pooled_q) return LCSA_EINVAL;
     if (!same_geom(geom, cache->geom)) return LCSA_EINVAL;

@@ -94,6 +94,10 @@ hipError_t launch_select(const KGeom &g, const KCache &c, const float *pooled_q,
                          int32_t *sel_idx, int32_t *sel_cnt, float *gap, int max_cand,
                          hipStream_t stream);
 
+// The same with the pooling of the chunk's queries folded in: q is pooled per block (written to pooled_q too).
+hipError_t launch_pool_select(const KGeom &g, const KCache &c, const void *q, int64_t q_st, int64_t q_sh, float *pooled_q,
+                              int32_t *sel_idx, int32_t *sel_cnt, float *gap, int max_cand, hipStream_t stream);
+
 hipError_t launch_attn_generic(const KGeom &g, const KCache &c, const void *q, int64_t q_st, int64_t q_sh,
                                const int32_t *sel_idx, const int32_t *sel_cnt,
                                void *o, int64_t o_st, int64_t o_sh, float *lse, float scale,

@@ -3,61 +3,12 @@
 // the new keys on the way.  One workgroup per (block, head); every global access is a
 // 16-byte vector per lane, consecutive lanes covering consecutive bytes of a token row.
 #include "lcsa_kernels.h"
+#include "lcsa_pool.h"
 
 namespace lcsa {
 namespace {
 
-constexpr int kThreads = 256;
-
-template <int VEC> struct Unpack;
-template <> struct Unpack<8> {   // 8 x bf16 in 16 bytes
-    static __device__ void to_float(const uint4 &u, float *f) {
-        const uint32_t w[4] = {u.x, u.y, u.z, u.w};
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            f[2 * i] = __uint_as_float(w[i] << 16);
-            f[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
-        }
-    }
-};
-template <> struct Unpack<4> {   // 4 x f32
-    static __device__ void to_float(const uint4 &u, float *f) {
-        f[0] = __uint_as_float(u.x); f[1] = __uint_as_float(u.y);
-        f[2] = __uint_as_float(u.z); f[3] = __uint_as_float(u.w);
-    }
-};
-
-struct TileRef {
-    int group, by, bx;   // group of tt frames within the call's tensor, tile coordinates
-    int vh, vw;          // valid rows / cols of the tile
-};
-
-__device__ inline TileRef tile_ref(const KGeom &g, int block) {
-    TileRef t;
-    t.group = block / g.nb;
-    int tile = block - t.group * g.nb;
-    t.by = tile / g.tx;
-    t.bx = tile - t.by * g.tx;
-    t.vh = min(g.th, g.H - t.by * g.th);
-    t.vw = min(g.tw, g.W - t.bx * g.tw);
-    return t;
-}
-
-// Sum over the row-groups held in LDS and write the mean of the block.
-template <int VEC>
-__device__ inline void finish_pool(float *red, const float *acc, int rg, int j, int lpr, int rows_par,
-                                   bool active, int d, int count, float *out) {
-    if (active) {
-#pragma unroll
-        for (int e = 0; e < VEC; ++e) red[rg * d + j * VEC + e] = acc[e];
-    }
-    __syncthreads();
-    for (int c = threadIdx.x; c < d; c += kThreads) {
-        float s = 0.f;
-        for (int r = 0; r < rows_par; ++r) s += red[r * d + c];
-        out[c] = s / (float)count;
-    }
-}
+using namespace pooling;
 
 // ---------------------------------------------------------------------------------------------
 // pooled[head][block][c] = mean over the block's valid tokens.      grid (n_groups*nb, heads)
@@ -71,33 +22,10 @@ __global__ __launch_bounds__(kThreads) void pool_kernel(KGeom g, const char *x, 
     const int rows_par = kThreads / lpr;       // token rows in flight
     const int rg = threadIdx.x / lpr, j = threadIdx.x - rg * lpr;
     const bool active = rg < rows_par;
-    constexpr int ELT = 16 / VEC;
     float acc[VEC];
 #pragma unroll
     for (int e = 0; e < VEC; ++e) acc[e] = 0.f;
-    if (active) {
-        // 8 token rows per lane are requested before any is consumed, so the loads overlap
-        for (int tok0 = rg; tok0 < g.bt; tok0 += 8 * rows_par) {
-            uint4 u[8];
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const int tok = tok0 + i * rows_par;
-                int ft, r, c;
-                u[i] = make_uint4(0, 0, 0, 0);
-                if (block_token(g, tok, t.vh, t.vw, ft, r, c)) {
-                    const int64_t token = raster_token(g, t.group, ft, t.by * g.th + r, t.bx * g.tw + c);
-                    u[i] = *(const uint4 *)(x + (token * st + (int64_t)head * sh + j * VEC) * ELT);
-                }
-            }
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                float f[VEC];
-                Unpack<VEC>::to_float(u[i], f);       // zeros for padding add nothing
-#pragma unroll
-                for (int e = 0; e < VEC; ++e) acc[e] += f[e];
-            }
-        }
-    }
+    if (active) accumulate_block<VEC>(g, t, x, st, sh, head, rg, j, rows_par, acc);
     finish_pool<VEC>(red, acc, rg, j, lpr, rows_par, active, g.d, g.tt * t.vh * t.vw,
                      pooled + ((int64_t)head * n_blocks + block) * g.d);
 }

@@ -5,6 +5,7 @@
 // bitwise search over order-preserving integer keys with ballot/popcount and emits the kept ids
 // in ascending order with ballot prefix counts.  No sort, no atomics, fully deterministic.
 #include "lcsa_kernels.h"
+#include "lcsa_pool.h"
 
 namespace lcsa {
 namespace {
@@ -22,13 +23,20 @@ __device__ inline float key_to_float(uint32_t key) {
 __device__ inline int wave_count(bool p) { return __popcll(__ballot(p)); }
 
 constexpr int kSelThreads = 256;
+static_assert(kSelThreads == pooling::kThreads, "the fused kernel pools with the pooling kernel's thread layout");
 
+// VEC = 0: the pooled queries are given.  VEC = 8 (bf16) or 4 (f32): the kernel first pools its own query
+// block from q, exactly as the pooling kernel would (same code, same summation order), and also writes
+// the mean to pooled_out: one launch and one pass over Q less per layer call.
+template <int VEC>
 __global__ __launch_bounds__(kSelThreads) void select_kernel(KGeom g, KCache c, const float *__restrict__ pooled_q,
+                                                             const char *__restrict__ x, int64_t st, int64_t sh,
+                                                             float *__restrict__ pooled_out,
                                                              int32_t *__restrict__ sel_idx, int32_t *__restrict__ sel_cnt,
                                                              float *__restrict__ gap) {
     extern __shared__ float smem[];
     float *qs = smem;                                  // [d] pooled query of this row
-    uint32_t *keys = (uint32_t *)(smem + g.d);         // [n] ordered keys of the admissible blocks
+    uint32_t *keys = (uint32_t *)(smem + g.d);         // [n] ordered keys of the admissible blocks (after pooling's partial sums)
     const int qb = blockIdx.x, head = blockIdx.y, tid = threadIdx.x, lane = tid & 63;
     const int n_qb = g.q_groups * g.nb;
     const int tile = qb % g.nb, by = tile / g.tx, bx = tile - by * g.tx;
@@ -39,7 +47,31 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(KGeom g, KCache c, 
     const int n = c.valid * nwin;                      // admissible key blocks, in ascending id order
     const int64_t row = (int64_t)head * n_qb + qb;
 
-    for (int i = tid; i < g.d; i += kSelThreads) qs[i] = pooled_q[row * g.d + i];
+    if constexpr (VEC == 0) {
+        for (int i = tid; i < g.d; i += kSelThreads) qs[i] = pooled_q[row * g.d + i];
+    } else {
+        float *red = smem + g.d;                       // [kSelThreads * VEC] partial sums per row group
+        const pooling::TileRef t = pooling::tile_ref(g, qb);
+        const int lpr = g.d / VEC, rows_par = kSelThreads / lpr;
+        const int rg = tid / lpr, j = tid - rg * lpr;
+        float acc[VEC];
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) acc[e] = 0.f;
+        if (rg < rows_par) {
+            pooling::accumulate_block<VEC>(g, t, x, st, sh, head, rg, j, rows_par, acc);
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) red[rg * g.d + j * VEC + e] = acc[e];
+        }
+        __syncthreads();
+        const int count = g.tt * t.vh * t.vw;
+        for (int ch = tid; ch < g.d; ch += kSelThreads) {
+            float sum = 0.f;
+            for (int r = 0; r < rows_par; ++r) sum += red[r * g.d + ch];
+            const float mean = sum / (float)count;
+            qs[ch] = mean;
+            pooled_out[row * g.d + ch] = mean;
+        }
+    }
     __syncthreads();
 
     // candidate ci -> (visible group f, tile t); key-block id = f*nb + t grows with ci
@@ -169,7 +201,19 @@ hipError_t launch_select(const KGeom &g, const KCache &c, const float *pooled_q,
                          int32_t *sel_idx, int32_t *sel_cnt, float *gap, int max_cand, hipStream_t stream) {
     dim3 grid(g.q_groups * g.nb, g.heads);
     const size_t lds = (size_t)(g.d + max_cand) * sizeof(float);
-    select_kernel<<<grid, kSelThreads, lds, stream>>>(g, c, pooled_q, sel_idx, sel_cnt, gap);
+    select_kernel<0><<<grid, kSelThreads, lds, stream>>>(g, c, pooled_q, nullptr, 0, 0, nullptr, sel_idx, sel_cnt, gap);
+    return hipGetLastError();
+}
+
+hipError_t launch_pool_select(const KGeom &g, const KCache &c, const void *q, int64_t q_st, int64_t q_sh, float *pooled_q,
+                              int32_t *sel_idx, int32_t *sel_cnt, float *gap, int max_cand, hipStream_t stream) {
+    dim3 grid(g.q_groups * g.nb, g.heads);
+    const int vec = g.bf16 ? 8 : 4;
+    const size_t lds = (size_t)(g.d + (max_cand > kSelThreads * vec ? max_cand : kSelThreads * vec)) * sizeof(float);
+    if (g.bf16)
+        select_kernel<8><<<grid, kSelThreads, lds, stream>>>(g, c, nullptr, (const char *)q, q_st, q_sh, pooled_q, sel_idx, sel_cnt, gap);
+    else
+        select_kernel<4><<<grid, kSelThreads, lds, stream>>>(g, c, nullptr, (const char *)q, q_st, q_sh, pooled_q, sel_idx, sel_cnt, gap);
     return hipGetLastError();
 }
 

@@ -205,6 +205,9 @@ class Pipeline:
         K, V = self.model.visible()
         pq = B.lcsa_pool_blocks(g, qd, g.q_frames)
         sel_idx, sel_cnt, gap = B.lcsa_select_blocks(g, pq, self.cache)
+        # the fused call must give the very same bits as the two calls
+        f_pq, f_idx, f_cnt, f_gap = B.lcsa_pool_select_blocks(g, qd, self.cache)
+        assert torch.equal(f_pq, pq) and torch.equal(f_idx, sel_idx) and torch.equal(f_cnt, sel_cnt) and torch.equal(f_gap, gap)
         lse = torch.empty(qd.shape[0], g.heads, dtype=torch.float32, device="cuda") if check_lse else None
         o = B.lcsa_sparse_attn_fwd(g, qd, self.cache, sel_idx, sel_cnt, lse=lse, scale=scale)
         torch.cuda.synchronize()

@@ -104,6 +104,9 @@ def test_host_side_validation_without_gpu():
     other = B.Geom(**{**PAPER, "grid_w": 80}).c()
     assert L.lcsa_select_blocks(ctypes.byref(other), fake, h, fake, fake, None, None) == -1
     assert L.lcsa_select_blocks(ctypes.byref(gc), None, h, fake, fake, None, None) == -1
+    assert L.lcsa_pool_select_blocks(ctypes.byref(gc), fake, 1536, 128, h, fake, fake, fake, None, None) == -1   # empty cache
+    assert L.lcsa_pool_select_blocks(ctypes.byref(gc), fake, 1536, 128, None, fake, fake, fake, None, None) == -1
+    assert L.lcsa_pool_select_blocks(ctypes.byref(gc), fake, 64, 128, h, fake, fake, fake, None, None) == -1
     # eviction policy: host-only switch, valid values only, importance needs a non-empty cache
     assert L.lcsa_cache_eviction(h) == B.LCSA_EVICT_SLIDING and L.lcsa_cache_order_device(h) is None
     assert L.lcsa_cache_set_eviction(h, 3) == -1 and L.lcsa_cache_set_eviction(h, -1) == -1
