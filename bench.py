@@ -54,9 +54,7 @@ def main() -> int:
     ap.add_argument("--eviction", default="sliding", choices=["sliding", "headwise", "uniform"],
                     help="KV-cache eviction: the paper's default sliding window, or importance-based (adds lcsa_block_importance to every layer call)")
     ap.add_argument("--graph", action="store_true",
-                    help="replay the layer calls of a step from captured HIP graphs; needs the device-side slot table of an "
-                         "importance policy: with --eviction sliding the head-wise policy runs unscored, which evicts the oldest "
-                         "frames exactly like the sliding window")
+                    help="replay the layer calls of a step from captured HIP graphs (the caches are full when they are recorded)")
     ap.add_argument("--two-calls", action="store_true",
                     help="pool and select with lcsa_pool_blocks + lcsa_select_blocks instead of the fused lcsa_pool_select_blocks")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -95,8 +93,6 @@ def main() -> int:
     policy = {"sliding": B.LCSA_EVICT_SLIDING, "headwise": B.LCSA_EVICT_IMPORTANCE_HEADWISE,
               "uniform": B.LCSA_EVICT_IMPORTANCE_UNIFORM}[args.eviction]
     scoring = policy != B.LCSA_EVICT_SLIDING
-    if args.graph and not scoring:
-        policy = B.LCSA_EVICT_IMPORTANCE_HEADWISE       # unscored: oldest first, with the ring position kept on the device
 
     def dev(x):
         return torch.from_numpy(wl.bf16_bits(x).view(np.int16)).view(torch.bfloat16).cuda()
@@ -208,15 +204,24 @@ def main() -> int:
     # back-to-back bf16 matrix instructions on registers, and a 1 GiB device-to-device copy
     prop = torch.cuda.get_device_properties(0)
     n_cu = prop.multi_processor_count
-    probe_out = torch.empty(n_cu * 2 * 512, dtype=torch.float32, device="cuda")
-    probe_iters = 4000
-    B.lcsa_probe_mfma_bf16(n_cu * 2, 200, probe_out)
     pe = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
-    pe[0].record()
-    B.lcsa_probe_mfma_bf16(n_cu * 2, probe_iters, probe_out)
-    pe[1].record()
-    torch.cuda.synchronize()
-    probe_tflops = n_cu * 2 * 8 * probe_iters * 32 * 32768.0 / (pe[0].elapsed_time(pe[1]) * 1e-3) / 1e12
+    probe_tflops = None
+    probe_path = os.path.join(ROOT, "libbench_probe.so")      # bench-only shared object, built by __graft_entry__.build()
+    if os.path.exists(probe_path):
+        import ctypes
+        probe = ctypes.CDLL(probe_path).bench_probe_mfma_bf16
+        probe.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p]
+        probe.restype = ctypes.c_int32
+        probe_out = torch.empty(n_cu * 2 * 512, dtype=torch.float32, device="cuda")
+        probe_iters = 4000
+        cur = torch.cuda.current_stream().cuda_stream
+        assert probe(probe_out.data_ptr(), n_cu * 2, 200, cur) == 0
+        pe[0].record()
+        assert probe(probe_out.data_ptr(), n_cu * 2, probe_iters, cur) == 0
+        pe[1].record()
+        torch.cuda.synchronize()
+        probe_tflops = n_cu * 2 * 8 * probe_iters * 32 * 32768.0 / (pe[0].elapsed_time(pe[1]) * 1e-3) / 1e12
+        del probe_out
     csrc = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
     cdst = torch.empty_like(csrc)
     cdst.copy_(csrc)
@@ -226,7 +231,7 @@ def main() -> int:
     pe[1].record()
     torch.cuda.synchronize()
     copy_gbs = 5 * 2 * float(1 << 30) / (pe[0].elapsed_time(pe[1]) * 1e-3) / 1e9
-    del csrc, cdst, probe_out
+    del csrc, cdst
 
     # ---- algorithmic work of one attention launch (from the selection actually made) ---------------
     ty, tx = -(-w.grid_h // w.tile_h), -(-w.grid_w // w.tile_w)
@@ -287,7 +292,7 @@ def main() -> int:
                        {"pool_select_blocks": round((pool_bytes + select_bytes) / (brk[2] * 1e-3) / 1e9, 1)})},
         "device": {"name": prop.name, "compute_units": n_cu,
                    "nominal_peak_tflops": PEAK_BF16_TFLOPS, "nominal_hbm_gbs": 8000.0},
-        "measured_peaks": {"mfma_bf16_register_loop_tflops": round(probe_tflops, 1),
+        "measured_peaks": {"mfma_bf16_register_loop_tflops": round(probe_tflops, 1) if probe_tflops else None,
                            "device_copy_gbs": round(copy_gbs, 1)},
         "roofline": {"kernel": "attn_mfma_kernel", "bound": "mfma", "achieved": round(achieved, 2),
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
@@ -296,7 +301,7 @@ def main() -> int:
                      "issued_tflops": round(issued_flop / (attn_avg_ms * 1e-3) / 1e12, 2),
                      "avg_launch_ms": round(attn_avg_ms, 5), "min_launch_ms": round(float(attn_ms.min()), 5),
                      # beside the nominal peak: the same figure against what a register-only MFMA loop sustains here
-                     "frac_of_measured_mfma_loop": round(achieved / probe_tflops, 4)},
+                     "frac_of_measured_mfma_loop": round(achieved / probe_tflops, 4) if probe_tflops else None},
         "setup_s": round(setup_s, 1),
     }
 

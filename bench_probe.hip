@@ -1,10 +1,12 @@
-// Measurement aid: what the matrix cores of this chip sustain on a loop that does nothing else.
-// Every wavefront runs back-to-back v_mfma_f32_32x32x16_bf16 on four independent accumulators
-// with operands that stay in registers (pseudo-random bf16 values, so that the data paths
-// toggle as they do on real inputs).  The benchmark quotes the rate next to the nominal peak.
-#include "lcsa_kernels.h"
+// Measurement aid of bench.py, built into its own shared object (libbench_probe.so); not part of the library.
+//
+// What the matrix cores of this chip sustain on a loop that does nothing else: every wavefront runs
+// back-to-back v_mfma_f32_32x32x16_bf16 on four independent accumulators with operands that stay in
+// registers (pseudo-random bf16 values, so that the data paths toggle as they do on real inputs).  The
+// benchmark quotes the rate next to the nominal peak.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
 
-namespace lcsa {
 namespace {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
@@ -46,9 +48,11 @@ __global__ __launch_bounds__(512) void probe_mfma_kernel(float *out, int iters) 
 
 } // namespace
 
-hipError_t launch_probe_mfma(float *out, int n_blocks, int iters, hipStream_t stream) {
-    probe_mfma_kernel<<<dim3(n_blocks), 512, 0, stream>>>(out, iters);
-    return hipGetLastError();
+// Runs n_blocks workgroups of 8 wavefronts, every wavefront issuing 32*iters matrix instructions (32768 flop
+// each).  out: device float [n_blocks*512], one checksum per thread.  Returns 0, -1 on bad arguments, -3 on a
+// launch error.
+extern "C" int32_t bench_probe_mfma_bf16(float *out, int32_t n_blocks, int32_t iters, void *stream) {
+    if (!out || n_blocks < 1 || n_blocks > 65536 || iters < 1 || iters > (1 << 20)) return -1;
+    probe_mfma_kernel<<<dim3(n_blocks), 512, 0, (hipStream_t)stream>>>(out, iters);
+    return hipGetLastError() == hipSuccess ? 0 : -3;
 }
-
-} // namespace lcsa

@@ -14,9 +14,17 @@
  *     library never allocates or frees device memory and never synchronises:
  *     each call validates its arguments on the host, enqueues kernels on the
  *     given stream (a hipStream_t passed as void*, NULL = default stream) and
- *     returns.  The cache's ring position advances on the host at enqueue time,
- *     so all calls that touch one cache must be issued in program order on one
- *     stream.
+ *     returns.  The number of visible frames advances on the host at enqueue time
+ *     and the slot positions advance on the device in stream order, so all calls
+ *     that touch one cache must be issued in program order on one stream.
+ *   - HIP graphs: a sequence of calls recorded by stream capture replays correctly,
+ *     chunk after chunk, provided the cache was FULL (valid frames = cache_frames)
+ *     when it was recorded: from then on every layer call has the same arguments and
+ *     launch shapes, and where the new frames go is decided on the device (sliding
+ *     window: a ring position the append launch advances; importance policies: the
+ *     slot table the eviction launch rewrites).  lcsa_kv_cache_append on a capturing
+ *     stream with a cache that is not full returns LCSA_EUNSUPPORTED.  Replays do not
+ *     move the host's copy of the ring position (lcsa_cache_frame_slot).
  *   - Tokens of a tensor are in raster order: token = (frame*grid_h + row)*grid_w + col.
  *     Element (token, head, c) of x is x[token*stride_tok + head*stride_head + c];
  *     strides are in elements, c is contiguous.  Base pointers must be 16-byte
@@ -99,13 +107,27 @@ int32_t lcsa_cache_valid_frames(const lcsa_cache *cache);
  * group that holds visible frame f (0 = oldest) is row lcsa_cache_frame_slot(cache, f)*nb + tile.
  */
 const float *lcsa_cache_pooled_k_device(const lcsa_cache *cache);
-int32_t lcsa_cache_frame_slot(const lcsa_cache *cache, int32_t frame);   /* sliding-window policy only */
+int32_t lcsa_cache_frame_slot(const lcsa_cache *cache, int32_t frame);   /* sliding-window policy only; counts enqueued
+                                                                            appends, not replays of a captured one */
+/*
+ * device uint32 [heads][(cache_frames/tile_t)*nb], by ring slot like the pooled keys: how many values of V
+ * the append clamped to +-65504 when it stored that block (see lcsa_kv_cache_append; always 0 for layouts
+ * that store V as given).  Entries of slots that hold no visible group are undefined.
+ */
+const uint32_t *lcsa_cache_v_clamped_device(const lcsa_cache *cache);
 
 /*
  * Appends the keys and values of n_frames new frames (device, raster order, the cache's
  * dtype, shared strides) and evicts frames beyond the capacity: the oldest ones under
  * sliding-window eviction, the paper's default (see lcsa_cache_set_eviction for the alternative).  Also stores the block means of the new keys (Sec. 3.2
  * average pooling) for lcsa_select_blocks.  1 <= n_frames <= cache_frames, a multiple of tile_t.
+ *
+ * Range of V.  For bf16 with head_dim = 128 and 128-token blocks (the matrix-core path) V is stored as
+ * IEEE half, which the second matrix product of lcsa_sparse_attn_fwd runs in: every bf16 value with
+ * 2^-14 <= |v| <= 65280 is stored exactly; smaller magnitudes round to the nearest multiple of 2^-24
+ * (absolute error at most 2^-25, zero below that); |v| >= 65536 and infinities are CLAMPED to +-65504 and
+ * counted per block (lcsa_cache_v_clamped_device), NaN stays NaN.  Attention over clamped values is the
+ * attention of eq. (1) on the clamped V.  Every other configuration stores V as given.
  */
 int32_t lcsa_kv_cache_append(lcsa_cache *cache, const void *k, const void *v,
                              int64_t stride_tok, int64_t stride_head,
@@ -192,7 +214,8 @@ int32_t lcsa_pool_select_blocks(const lcsa_geom *geom, const void *q, int64_t q_
  * frames, each with its own strides.  lse: device float [token][head] or NULL, natural
  * log of the softmax denominator.  scale <= 0 selects 1/sqrt(head_dim).  Products are
  * formed from the stored element type with float accumulation and a float online
- * softmax; on the matrix-core path probabilities and V enter the second product as IEEE half.
+ * softmax; on the matrix-core path probabilities and V enter the second product as IEEE half
+ * (range of V: see lcsa_kv_cache_append).
  * Rows with sel_cnt = 0 produce zeros (lse = -inf).  Counts outside [0, topk] and ids outside the
  * visible blocks are clamped into range by the kernels (the row's result is then meaningless, but
  * nothing outside the cache is read).
@@ -203,17 +226,6 @@ int32_t lcsa_sparse_attn_fwd(const lcsa_geom *geom,
                              const int32_t *sel_idx, const int32_t *sel_cnt,
                              void *o, int64_t o_stride_tok, int64_t o_stride_head,
                              float *lse, float scale, void *stream);
-
-/* ---- measurement aid (not part of the method) ---------------------------------------------------- */
-
-/*
- * Runs n_blocks workgroups of 8 wavefronts, every wavefront issuing 32*iters back-to-back
- * v_mfma_f32_32x32x16_bf16 (32768 flop each) on operands that stay in registers: the matrix rate
- * this chip sustains when nothing else limits it, which a benchmark can quote beside the nominal
- * peak.  out: device float [n_blocks*512], receives one checksum per thread.
- * 1 <= n_blocks <= 65536, 1 <= iters <= 2^20, else LCSA_EINVAL.
- */
-int32_t lcsa_probe_mfma_bf16(float *out, int32_t n_blocks, int32_t iters, void *stream);
 
 /* Static, human-readable text for a status code. */
 const char *lcsa_status_string(int32_t status);

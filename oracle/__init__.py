@@ -273,14 +273,36 @@ class ImportanceCache:
             for e, x in zip(self.groups[h], imp[h]):
                 e[2] = float(x)
 
-    def append(self, k: np.ndarray, v: np.ndarray, n_frames: int) -> None:
+    def victims(self, n_frames: int) -> list[list[int]]:
+        """Per head, the visible groups (positions in temporal order, ascending) that an append of n_frames
+        frames would drop: lowest importance first, equal importance: the older one first."""
+        n_new = n_frames // self.tile_t
+        out = []
+        for lst in self.groups:
+            alive = list(range(len(lst)))
+            gone = []
+            for _ in range(max(0, len(lst) + n_new - self.capacity)):
+                victim = min(alive, key=lambda i: (lst[i][2], i))
+                alive.remove(victim)
+                gone.append(victim)
+            out.append(sorted(gone))
+        return out
+
+    def append(self, k: np.ndarray, v: np.ndarray, n_frames: int, victims=None) -> None:
+        """victims: per head, the positions to drop instead of the model's own choice (same count).  A test
+        passes the decision of the implementation under test here after checking that it is one this
+        model's importances allow within the stated near-tie margin, so that both sides keep holding the
+        same frames afterwards."""
         assert n_frames % self.tile_t == 0
         n_new = n_frames // self.tile_t
         per = k.shape[0] // n_new
+        own = self.victims(n_frames)
+        if victims is None:
+            victims = own
         for h in range(self.heads):
             lst = self.groups[h]
-            for _ in range(max(0, len(lst) + n_new - self.capacity)):
-                victim = min(range(len(lst)), key=lambda i: (lst[i][2], i))     # lowest importance, then oldest
+            assert len(victims[h]) == len(own[h]) and len(set(victims[h])) == len(victims[h])
+            for victim in sorted(victims[h], reverse=True):
                 lst.pop(victim)
             for e in lst:
                 e[2] = 0.0
@@ -288,6 +310,11 @@ class ImportanceCache:
                 lst.append([np.array(k[gi * per:(gi + 1) * per, h]), np.array(v[gi * per:(gi + 1) * per, h]), 0.0,
                             self.births + gi])
         self.births += n_new
+
+    def importances(self) -> np.ndarray:
+        """[heads][visible groups]: the importance each visible group currently carries (after set_importance:
+        the scores, summed over heads under the uniform policy; after an append: zeros)."""
+        return np.array([[e[2] for e in lst] for lst in self.groups], np.float64)
 
     @property
     def valid_frames(self) -> int:

@@ -14,8 +14,7 @@ from dataclasses import dataclass
 import torch  # imported first so that the HIP runtime torch ships is the one the library binds to
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-# LCSA_LIBRARY may name another build of the same library (e.g. an experimental kernel variant)
-LIB_PATH = os.environ.get("LCSA_LIBRARY") or os.path.join(_HERE, "liblcsa.so")
+LIB_PATH = os.path.join(_HERE, "liblcsa.so")
 
 LCSA_EVICT_SLIDING, LCSA_EVICT_IMPORTANCE_HEADWISE, LCSA_EVICT_IMPORTANCE_UNIFORM = 0, 1, 2
 LCSA_F32, LCSA_BF16 = 0, 1
@@ -98,7 +97,8 @@ def lib():
         L.lcsa_pool_blocks.argtypes = [_gp, _vp, _i64, _i64, _i32, _vp, _vp]
         L.lcsa_select_blocks.argtypes = [_gp, _vp, _vp, _vp, _vp, _vp, _vp]
         L.lcsa_sparse_attn_fwd.argtypes = [_gp, _vp, _i64, _i64, _vp, _vp, _vp, _vp, _i64, _i64, _vp, _f32, _vp]
-        L.lcsa_probe_mfma_bf16.argtypes = [_vp, _i32, _i32, _vp]
+        L.lcsa_cache_v_clamped_device.argtypes = [_vp]
+        L.lcsa_cache_v_clamped_device.restype = _vp
         L.lcsa_pool_select_blocks.argtypes = [_gp, _vp, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _vp]
         L.lcsa_cache_set_eviction.argtypes = [_vp, _i32]
         L.lcsa_cache_eviction.argtypes = [_vp]
@@ -112,7 +112,7 @@ def lib():
         L.lcsa_last_hip_error.restype = ctypes.c_char_p
         for f in ("lcsa_cache_init", "lcsa_cache_reset", "lcsa_cache_valid_frames", "lcsa_cache_frame_slot",
                   "lcsa_kv_cache_append", "lcsa_pool_blocks", "lcsa_select_blocks", "lcsa_sparse_attn_fwd",
-                  "lcsa_probe_mfma_bf16", "lcsa_pool_select_blocks", "lcsa_cache_set_eviction", "lcsa_cache_eviction", "lcsa_block_importance"):
+                  "lcsa_pool_select_blocks", "lcsa_cache_set_eviction", "lcsa_cache_eviction", "lcsa_block_importance"):
             getattr(L, f).restype = _i32
         _lib = L
     return _lib
@@ -138,15 +138,6 @@ def _tok(x: torch.Tensor):
     if not x.is_cuda or x.dim() != 3 or x.stride(2) != 1:
         raise LcsaError("expected a device tensor [tokens][heads][d] with contiguous d")
     return x.data_ptr(), x.stride(0), x.stride(1)
-
-
-def lcsa_probe_mfma_bf16(n_blocks: int, iters: int, out: torch.Tensor | None = None, stream=None) -> torch.Tensor:
-    """Measurement aid: n_blocks x 8 wavefronts x 32*iters back-to-back bf16 matrix instructions."""
-    if out is None:
-        out = torch.empty(n_blocks * 512, dtype=torch.float32, device="cuda")
-    assert out.is_contiguous() and out.dtype == torch.float32 and out.numel() >= n_blocks * 512
-    _check(lib().lcsa_probe_mfma_bf16(out.data_ptr(), n_blocks, iters, _stream(stream)), "lcsa_probe_mfma_bf16")
-    return out
 
 
 def lcsa_status_string(status: int) -> str:
@@ -244,6 +235,16 @@ def lcsa_cache_pooled_k(cache: Cache) -> torch.Tensor:
     rows = g.cache_frames // g.tile_t * g.nb
     n = g.heads * rows * g.head_dim
     return cache.storage[off:off + 4 * n].view(torch.float32).view(g.heads, rows, g.head_dim)
+
+
+def lcsa_cache_v_clamped(cache: Cache) -> torch.Tensor:
+    """int32 view [heads][(cache_frames/tile_t)*nb] over the cache storage (ring-slot order): values of V that the
+    append clamped to half's range when it stored that block."""
+    g = cache.geom
+    ptr = lib().lcsa_cache_v_clamped_device(cache.handle)
+    off = ptr - cache.storage.data_ptr()
+    rows = g.cache_frames // g.tile_t * g.nb
+    return cache.storage[off:off + 4 * g.heads * rows].view(torch.int32).view(g.heads, rows)
 
 
 def lcsa_kv_cache_append(cache: Cache, k: torch.Tensor, v: torch.Tensor, n_frames: int, stream=None) -> None:

@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "liblcsa.so")
 SOURCES = ["lcsa_host.hip", "lcsa_pool_append.hip", "lcsa_select.hip", "lcsa_attn_generic.hip", "lcsa_attn_mfma.hip",
-           "lcsa_probe.hip", "lcsa_evict.hip"]
+           "lcsa_evict.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
          # packed-fp32 VALU forms are kept out of the generated code on purpose
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -31,5 +31,20 @@ def build(verbose: bool = False) -> str:
     return LIB
 
 
+def build_bench_aids(verbose: bool = False) -> str:
+    """bench.py's measurement aids (a register-only matrix-instruction loop), a shared object of their own."""
+    root = os.path.dirname(HERE)
+    out = os.path.join(root, "libbench_probe.so")
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    cmd = [hipcc, *FLAGS, "-o", out, os.path.join(root, "bench_probe.hip")]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + "\n".join(l for l in res.stderr.splitlines() if "packed-fp32-ops" not in l))
+    return out
+
+
 if __name__ == "__main__":
     print(build(verbose=True))
+    print(build_bench_aids(verbose=True))

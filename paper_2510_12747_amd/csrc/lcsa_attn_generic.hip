@@ -67,6 +67,7 @@ __global__ __launch_bounds__(64 * kWaves) void attn_generic_kernel(
     const int cnt = min(max(sel_cnt[row], 0), g.topk);       // a row holds at most topk ids
     const int32_t *sel = sel_idx + row * g.topk;
     const T *kc = (const T *)c.k, *vc = (const T *)c.v;
+    const int start = ring_start(c, g);
 
     // every wavefront walks the same loop structure so that workgroup barriers line up;
     // wavefronts whose token is padding compute on a clamped token and store nothing
@@ -84,7 +85,7 @@ __global__ __launch_bounds__(64 * kWaves) void attn_generic_kernel(
             const int kb = min(max(sel[b], 0), c.valid * g.nb - 1);   // ids outside the cache must not become wild addresses
             const int f = kb / g.nb, kt = kb - f * g.nb, kby = kt / g.tx, kbx = kt - kby * g.tx;
             const int vh = min(g.th, g.H - kby * g.th), vw = min(g.tw, g.W - kbx * g.tw);
-            const int slot = cache_slot(c, g, head, f);
+            const int slot = cache_slot(c, g, start, head, f);
             const int64_t tbase = (((int64_t)head * g.cap + slot) * g.nb + kt) * g.bt * g.d;
             for (int base = 0; base < g.bt; base += 64) {
                 const int key = base + lane;

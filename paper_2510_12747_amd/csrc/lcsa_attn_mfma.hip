@@ -109,12 +109,12 @@ __device__ inline float block_row_max(const f32x16 (&sc)[4], int nf) {
 
 // A selected key block as the loop wants it: ring-slot tile index and its number of valid keys.
 //   bits 0..23 tile index (slot*nb + tile), bits 24..30 valid keys - 1
-__device__ inline uint32_t pack_block(const KGeom &g, const KCache &c, int head, int kb, int ph, int pw) {
+__device__ inline uint32_t pack_block(const KGeom &g, const KCache &c, int start, int head, int kb, int ph, int pw) {
     kb = min(max(kb, 0), c.valid * g.nb - 1);          // ids outside the cache (corrupt input) must not become wild addresses
     const int f = kb / g.nb, kt = kb - f * g.nb;
     const int kby = kt / g.tx, kbx = kt - kby * g.tx;
     const int vh = kby == g.ty - 1 ? ph : g.th, vw = kbx == g.tx - 1 ? pw : g.tw;
-    return (uint32_t)(cache_slot(c, g, head, f) * g.nb + kt) | (uint32_t)(g.tt * vh * vw - 1) << 24;
+    return (uint32_t)(cache_slot(c, g, start, head, f) * g.nb + kt) | (uint32_t)(g.tt * vh * vw - 1) << 24;
 }
 __device__ inline int block_keys(uint32_t blk) { return (int)(blk >> 24) + 1; }
 
@@ -150,6 +150,7 @@ __global__ __launch_bounds__(512, 2) void attn_mfma_kernel(
     const int item = 2 * pair + grp8, other = 2 * pair + (grp8 ^ 1);
     const bool active = item < total_items;
     int head = 0, qb = 0, cnt = 0, other_cnt = 0;
+    const int start = ring_start(c, g);    // requested together with the counts and ids below
     int32_t first_ids = -1;                // selected block `lane` of this row, requested together with the count
     if (active) {
         item_row(item, head, qb);
@@ -194,7 +195,7 @@ __global__ __launch_bounds__(512, 2) void attn_mfma_kernel(
     const uint32_t vdst = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)((LCSA_LDS unsigned char *)v_lds) + wave * 8192);
     // selected blocks of this row, 64 at a time, one per lane, already turned into tile indices
     const int ph = g.H - (g.ty - 1) * g.th, pw = g.W - (g.tx - 1) * g.tw;   // extent of clipped edge tiles
-    uint32_t blk_chunk = lane < cnt ? pack_block(g, c, head, first_ids, ph, pw) : 0u;
+    uint32_t blk_chunk = lane < cnt ? pack_block(g, c, start, head, first_ids, ph, pw) : 0u;
     uint32_t blk = __builtin_amdgcn_readfirstlane(blk_chunk);
     if (cnt > 0 && wave < key_groups(blk)) {
 #pragma unroll
@@ -323,7 +324,7 @@ __global__ __launch_bounds__(512, 2) void attn_mfma_kernel(
             has_next = it + 1 < cnt;
             if (has_next) {
                 if (((it + 1) & 63) == 0) {
-                    blk_chunk = (it + 1 + lane) < cnt ? pack_block(g, c, head, sel[it + 1 + lane], ph, pw) : 0u;
+                    blk_chunk = (it + 1 + lane) < cnt ? pack_block(g, c, start, head, sel[it + 1 + lane], ph, pw) : 0u;
                     blk_next = __builtin_amdgcn_readlane(blk_chunk, 0);
                 } else {
                     blk_next = __builtin_amdgcn_readlane(blk_chunk, (it + 1) & 63);

@@ -36,6 +36,7 @@ __global__ __launch_bounds__(kThreads) void importance_rows_kernel(KGeom g, KCac
     const int wx = x1 - x0, nwin = (y1 - y0) * wx;
     const int n = c.valid * nwin;           // admissible key blocks; those of visible group f are [f*nwin, (f+1)*nwin)
     const int64_t row = (int64_t)head * n_qb + qb;
+    const int start = ring_start(c, g);
 
     for (int i = tid; i < g.d; i += kThreads) qs[i] = pooled_q[row * g.d + i];
     __syncthreads();
@@ -48,7 +49,7 @@ __global__ __launch_bounds__(kThreads) void importance_rows_kernel(KGeom g, KCac
             if (ci < n) {
                 const int f = ci / nwin, w = ci - f * nwin, wy = w / wx;
                 const int t = (y0 + wy) * g.tx + x0 + (w - wy * wx);
-                const int slot = cache_slot(c, g, head, f);
+                const int slot = cache_slot(c, g, start, head, f);
                 const float4 *kr = (const float4 *)(c.pooled + (((int64_t)head * g.cap + slot) * g.nb + t) * g.d);
                 for (int e4 = part; e4 < n4; e4 += 4) {
                     const float4 kk = kr[e4];

@@ -14,6 +14,8 @@ struct lcsa_cache {
     KGeom kg;
     KCache kc;
     size_t bytes;
+    int start;             // sliding window: ring slot of the oldest visible group as enqueued so far (host mirror of
+                           // the device words in kc.ring; replays of a captured append do not move it)
     int32_t policy;        // LCSA_EVICT_*
     int32_t *order;        // device [heads][cap]: visible group -> slot (importance-based policies)
     float *importance;     // device [heads][cap]: importance of the visible groups, from lcsa_block_importance
@@ -33,6 +35,13 @@ int32_t hip_status(hipError_t e) {
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
+// Is `stream` being recorded into a HIP graph?  (No GPU, or an error from the query: no.)
+bool stream_is_capturing(hipStream_t stream) {
+    hipStreamCaptureStatus st = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(stream, &st) != hipSuccess) { (void)hipGetLastError(); return false; }
+    return st != hipStreamCaptureStatusNone;
+}
+
 bool geom_ok(const lcsa_geom *g) {
     if (!g) return false;
     if (g->dtype != LCSA_F32 && g->dtype != LCSA_BF16) return false;
@@ -47,6 +56,7 @@ bool geom_ok(const lcsa_geom *g) {
     // index arithmetic in the kernels is 32-bit for block ids and 64-bit for elements
     const int64_t ty = (g->grid_h + g->tile_h - 1) / g->tile_h, tx = (g->grid_w + g->tile_w - 1) / g->tile_w;
     if (ty * tx * g->cache_frames > (1 << 24)) return false;
+    if (ty * tx * g->cache_frames * g->heads > (1ll << 30)) return false;      // one workgroup per (block, head) in a 1-D grid
     if ((int64_t)g->grid_h * g->grid_w * g->cache_frames > (1ll << 30)) return false;
     return true;
 }
@@ -73,7 +83,7 @@ bool same_geom(const lcsa_geom *a, const lcsa_geom &b) {
            a->cache_frames == b.cache_frames && a->dtype == b.dtype;
 }
 
-struct Layout { size_t k_off, v_off, pooled_off, order_off, imp_off, row_group_off, total; };
+struct Layout { size_t k_off, v_off, pooled_off, order_off, imp_off, row_group_off, ring_off, clamped_off, total; };
 
 Layout cache_layout(const KGeom &k) {
     const size_t elt = k.bf16 ? 2 : 4;
@@ -86,7 +96,9 @@ Layout cache_layout(const KGeom &k) {
     l.order_off = l.pooled_off + align_up(tiles * k.d * sizeof(float), 256);
     l.imp_off = l.order_off + align_up((size_t)k.heads * k.cap * sizeof(int32_t), 256);
     l.row_group_off = l.imp_off + align_up((size_t)k.heads * k.cap * sizeof(float), 256);
-    l.total = l.row_group_off + align_up((size_t)k.heads * k.q_groups * k.nb * k.cap * sizeof(float), 256);
+    l.ring_off = l.row_group_off + align_up((size_t)k.heads * k.q_groups * k.nb * k.cap * sizeof(float), 256);
+    l.clamped_off = l.ring_off + 256;
+    l.total = l.clamped_off + align_up(tiles * sizeof(uint32_t), 256);
     return l;
 }
 
@@ -120,7 +132,9 @@ int32_t lcsa_cache_init(lcsa_cache **out, const lcsa_geom *geom, void *device_me
     c->kc.k = base + l.k_off;
     c->kc.v = base + l.v_off;
     c->kc.pooled = (float *)(base + l.pooled_off);
-    c->kc.start = 0;
+    c->kc.v_clamped = (uint32_t *)(base + l.clamped_off);
+    c->kc.ring = (int32_t *)(base + l.ring_off);
+    c->start = 0;
     c->kc.valid = 0;
     c->kc.mfma_layout = kg.bf16 && kg.d == 128 && kg.bt == 128;
     c->kc.order = nullptr;
@@ -135,7 +149,7 @@ int32_t lcsa_cache_init(lcsa_cache **out, const lcsa_geom *geom, void *device_me
 
 int32_t lcsa_cache_reset(lcsa_cache *cache) {
     if (!cache) return LCSA_EINVAL;
-    cache->kc.start = 0;
+    cache->start = 0;
     cache->kc.valid = 0;
     cache->scored = false;
     return LCSA_OK;
@@ -150,7 +164,7 @@ int32_t lcsa_cache_set_eviction(lcsa_cache *cache, int32_t policy) {
     if (policy != LCSA_EVICT_SLIDING && cache->kg.cap > kMaxEvictGroups) return LCSA_EUNSUPPORTED;
     cache->policy = policy;
     cache->kc.order = policy == LCSA_EVICT_SLIDING ? nullptr : cache->order;
-    cache->kc.start = 0;
+    cache->start = 0;
     return LCSA_OK;
 }
 
@@ -166,10 +180,12 @@ int32_t lcsa_cache_valid_frames(const lcsa_cache *cache) {
 
 const float *lcsa_cache_pooled_k_device(const lcsa_cache *cache) { return cache ? cache->kc.pooled : nullptr; }
 
+const uint32_t *lcsa_cache_v_clamped_device(const lcsa_cache *cache) { return cache ? cache->kc.v_clamped : nullptr; }
+
 int32_t lcsa_cache_frame_slot(const lcsa_cache *cache, int32_t frame) {
     if (!cache || frame < 0 || frame >= cache->kc.valid * cache->kg.tt) return LCSA_EINVAL;
     if (cache->policy != LCSA_EVICT_SLIDING) return LCSA_EINVAL;      // per head, on the device: lcsa_cache_order_device
-    return slot_of_frame(cache->kc.start, cache->kg.cap, frame / cache->kg.tt);
+    return slot_of_frame(cache->start, cache->kg.cap, frame / cache->kg.tt);
 }
 
 int32_t lcsa_kv_cache_append(lcsa_cache *cache, const void *k, const void *v,
@@ -181,26 +197,28 @@ int32_t lcsa_kv_cache_append(lcsa_cache *cache, const void *k, const void *v,
     if ((int64_t)n_frames * kg.H * kg.W > (1ll << 30)) return LCSA_EINVAL;
     KCache &kc = cache->kc;
     const int n_groups = n_frames / kg.tt;
+    const int evict = kc.valid + n_groups > kg.cap ? kc.valid + n_groups - kg.cap : 0;
+    // The number of visible groups travels by value in every launch, so a captured call replays correctly only
+    // if that number no longer changes: the cache must be full when it is recorded.
+    if (kc.valid != kg.cap && stream_is_capturing((hipStream_t)stream)) return LCSA_EUNSUPPORTED;
     if (cache->policy != LCSA_EVICT_SLIDING) {
         // The least important visible groups make room (per head, or for all heads alike); the table of
         // slots is rewritten on the device, in stream order, before the tiles are written.
-        const int evict = kc.valid + n_groups > kg.cap ? kc.valid + n_groups - kg.cap : 0;
         hipError_t e = launch_evict(kg, cache->order, cache->importance, kc.valid, n_groups, evict,
                                     cache->policy == LCSA_EVICT_IMPORTANCE_UNIFORM, cache->scored, (hipStream_t)stream);
         if (e != hipSuccess) return hip_status(e);
         cache->scored = false;
-        e = launch_append(kg, kc, k, v, stride_tok, stride_head, n_groups, kc.valid - evict, (hipStream_t)stream);
+        e = launch_append(kg, kc, k, v, stride_tok, stride_head, n_groups, kc.valid - evict, false, (hipStream_t)stream);
         if (e != hipSuccess) return hip_status(e);
         kc.valid = kc.valid - evict + n_groups;
         return LCSA_OK;
     }
-    // New groups go into the slots right after the newest one; once the ring is full those are the
-    // slots of the oldest groups, which thereby leave the window.
-    const int first = slot_of_frame(kc.start, kg.cap, kc.valid);   // start + valid < 2*cap
-    hipError_t e = launch_append(kg, kc, k, v, stride_tok, stride_head, n_groups, first, (hipStream_t)stream);
+    // New groups go into the slots right after the newest one; once the ring is full those are the slots of
+    // the oldest groups, which thereby leave the window.  The position is a device word that the launch
+    // itself advances; the first append into an empty cache initialises it.
+    hipError_t e = launch_append(kg, kc, k, v, stride_tok, stride_head, n_groups, 0, kc.valid == 0, (hipStream_t)stream);
     if (e != hipSuccess) return hip_status(e);
-    const int evict = kc.valid + n_groups > kg.cap ? kc.valid + n_groups - kg.cap : 0;
-    kc.start = slot_of_frame(kc.start, kg.cap, evict);
+    cache->start = slot_of_frame(cache->start, kg.cap, evict);
     kc.valid = kc.valid + n_groups - evict;
     return LCSA_OK;
 }
@@ -271,11 +289,6 @@ int32_t lcsa_sparse_attn_fwd(const lcsa_geom *geom, const void *q, int64_t q_str
         : launch_attn_generic(kg, cache->kc, q, q_stride_tok, q_stride_head, sel_idx, sel_cnt,
                               o, o_stride_tok, o_stride_head, lse, scale, (hipStream_t)stream);
     return hip_status(e);
-}
-
-int32_t lcsa_probe_mfma_bf16(float *out, int32_t n_blocks, int32_t iters, void *stream) {
-    if (!out || n_blocks < 1 || n_blocks > 65536 || iters < 1 || iters > (1 << 20)) return LCSA_EINVAL;
-    return hip_status(launch_probe_mfma(out, n_blocks, iters, (hipStream_t)stream));
 }
 
 const char *lcsa_status_string(int32_t status) {

@@ -32,11 +32,15 @@ struct KGeom {
 struct KCache {
     void *k, *v;
     float *pooled;
-    int start;   // ring slot of the oldest visible group (sliding-window eviction)
+    uint32_t *v_clamped;   // [heads][cap*nb] by ring slot: V values of the block that the matrix-core layout clamped to half's range
+    // Sliding-window eviction: two device words.  ring[0] = slot the next appended group goes to (so the oldest
+    // visible group sits `valid` slots before it); ring[1] = arrival counter of the append launch in flight.
+    // Only the append kernels write them, in stream order, which is what lets a captured layer call replay.
+    int32_t *ring;
     int valid;   // visible groups
     int mfma_layout;
     // importance-based eviction: device table [heads][cap], visible group (0 = oldest) -> slot, per head;
-    // null under sliding-window eviction, where the slot follows from `start`
+    // null under sliding-window eviction, where the slot follows from ring[0]
     const int32_t *order;
 };
 
@@ -45,9 +49,17 @@ __host__ __device__ inline int slot_of_frame(int start, int cap, int f) {
     return s >= cap ? s - cap : s;
 }
 
-// Slot that holds visible group f (0 = oldest) of a head.
-__device__ inline int cache_slot(const KCache &c, const KGeom &g, int head, int f) {
-    return c.order ? c.order[head * g.cap + f] : slot_of_frame(c.start, g.cap, f);
+// Ring slot of the oldest visible group under sliding-window eviction; read once per kernel (no kernel that
+// reads it runs while an append on the same stream is still writing it).
+__device__ inline int ring_start(const KCache &c, const KGeom &g) {
+    if (c.order) return 0;
+    const int s = c.ring[0] - c.valid;
+    return s < 0 ? s + g.cap : s;
+}
+
+// Slot that holds visible group f (0 = oldest) of a head; start = ring_start(c, g).
+__device__ inline int cache_slot(const KCache &c, const KGeom &g, int start, int head, int f) {
+    return c.order ? c.order[head * g.cap + f] : slot_of_frame(start, g.cap, f);
 }
 
 // Block token i -> (frame within the group, row, col inside the tile) of a tile clipped to vh x vw.
@@ -70,11 +82,13 @@ __host__ __device__ inline int64_t raster_token(const KGeom &g, int group, int f
 hipError_t launch_pool(const KGeom &g, const void *x, int64_t stride_tok, int64_t stride_head,
                        int n_groups, float *pooled, hipStream_t stream);
 
-// Writes n_groups groups of frames: tiles of K, V and pooled K.  Sliding window (c.order null): into
-// ring slots first.. (mod cap).  Importance-based eviction: group i into the slot that c.order gives
-// visible group first + i of each head.
+// Writes n_groups groups of frames: tiles of K, V and pooled K.  Importance-based eviction (c.order set):
+// group i into the slot that c.order gives visible group first + i of each head.  Sliding window (c.order
+// null): into ring slots ring[0].. (mod cap), and the launch advances ring[0] by n_groups once every
+// workgroup has read it; fresh = the cache is empty and the ring words hold nothing yet: the groups go to
+// slots 0.. and the words are initialised.
 hipError_t launch_append(const KGeom &g, const KCache &c, const void *k, const void *v,
-                         int64_t stride_tok, int64_t stride_head, int n_groups, int first,
+                         int64_t stride_tok, int64_t stride_head, int n_groups, int first, bool fresh,
                          hipStream_t stream);
 
 // Importance of the visible groups from the coarse attention map of one chunk (appendix on KV-cache
@@ -107,9 +121,6 @@ hipError_t launch_attn_mfma(const KGeom &g, const KCache &c, const void *q, int6
                             const int32_t *sel_idx, const int32_t *sel_cnt,
                             void *o, int64_t o_st, int64_t o_sh, float *lse, float scale,
                             hipStream_t stream);
-
-// Measurement aid: n_blocks workgroups of 8 wavefronts, each wavefront issuing 32*iters matrix instructions.
-hipError_t launch_probe_mfma(float *out, int n_blocks, int iters, hipStream_t stream);
 
 // Largest number of admissible key blocks of any query block (host arithmetic).
 int max_candidates(const KGeom &g, int valid_groups);

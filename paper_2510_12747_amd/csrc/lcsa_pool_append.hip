@@ -2,6 +2,9 @@
 // append, which re-tiles K and V into the layout the attention kernels read and pools
 // the new keys on the way.  One workgroup per (block, head); every global access is a
 // 16-byte vector per lane, consecutive lanes covering consecutive bytes of a token row.
+// Workgroups are numbered head-fastest: the workgroups that are dispatched together then read
+// neighbouring pieces of the same token rows ([token][head][d] storage), which keeps the DRAM
+// pages they open busy.
 #include "lcsa_kernels.h"
 #include "lcsa_pool.h"
 
@@ -10,13 +13,42 @@ namespace {
 
 using namespace pooling;
 
+// Sliding-window eviction keeps its ring position in device memory (KCache::ring) so that a captured append
+// replays into the right slots.  Thread 0 of every workgroup of an append launch reads ring[0] (the slot the
+// launch's first group goes to), hands it to the workgroup through LDS, and then draws a ticket; the workgroup
+// that drew the last ticket, knowing that every other workgroup has read the word, advances it when it is done.
+// The ticket is requested at the start and looked at only at the end, so its latency hides behind the tile.
+// A launch into an empty cache (fresh) reads nothing: it starts at slot 0 and initialises both words.
+struct RingPos { int head_slot, ticket; };
+
+// Called by every thread (holds a workgroup barrier unless the ring is not in use); word = one int of LDS.
+__device__ inline RingPos ring_enter(const KCache &c, bool fresh, int *word) {
+    RingPos p = {0, -1};
+    if (c.order || fresh) return p;
+    if (threadIdx.x == 0) *word = c.ring[0];
+    __syncthreads();
+    p.head_slot = *word;
+    if (threadIdx.x == 0) p.ticket = atomicAdd(&c.ring[1], 1);
+    return p;
+}
+__device__ inline void ring_leave(const KCache &c, const KGeom &g, const RingPos &p, int n_groups, bool fresh) {
+    if (c.order || threadIdx.x != 0) return;
+    const int next = (p.head_slot + n_groups) % g.cap;
+    if (fresh) {
+        if (blockIdx.x == 0) { c.ring[0] = next; c.ring[1] = 0; }
+    } else if (p.ticket == (int)gridDim.x - 1) {
+        c.ring[0] = next;
+        c.ring[1] = 0;
+    }
+}
+
 // ---------------------------------------------------------------------------------------------
-// pooled[head][block][c] = mean over the block's valid tokens.      grid (n_groups*nb, heads)
+// pooled[head][block][c] = mean over the block's valid tokens.      grid n_groups*nb*heads
 template <int VEC>
 __global__ __launch_bounds__(kThreads) void pool_kernel(KGeom g, const char *x, int64_t st, int64_t sh,
                                                         int n_blocks, float *pooled) {
     __shared__ float red[kThreads * VEC];
-    const int block = blockIdx.x, head = blockIdx.y;
+    const int block = blockIdx.x / g.heads, head = blockIdx.x - block * g.heads;
     const TileRef t = tile_ref(g, block);
     const int lpr = g.d / VEC;                 // lanes per token row
     const int rows_par = kThreads / lpr;       // token rows in flight
@@ -32,14 +64,16 @@ __global__ __launch_bounds__(kThreads) void pool_kernel(KGeom g, const char *x, 
 
 // ---------------------------------------------------------------------------------------------
 // Cache append, generic tile image: K and V tiles row-major [bt][d], padded tokens zero;
-// pooled K written beside them.                                      grid (n_groups*nb, heads)
+// pooled K written beside them.                                      grid n_groups*nb*heads
 template <int VEC>
 __global__ __launch_bounds__(kThreads) void append_generic_kernel(KGeom g, KCache c, const char *k, const char *v,
-                                                                  int64_t st, int64_t sh, int first) {
+                                                                  int64_t st, int64_t sh, int first, int n_groups, bool fresh) {
     __shared__ float red[kThreads * VEC];
-    const int block = blockIdx.x, head = blockIdx.y;
+    __shared__ int ring_word;
+    const int block = blockIdx.x / g.heads, head = blockIdx.x - block * g.heads;
     const TileRef t = tile_ref(g, block);
-    const int slot = c.order ? c.order[head * g.cap + first + t.group] : (first + t.group) % g.cap;
+    const RingPos ring = ring_enter(c, fresh, &ring_word);
+    const int slot = c.order ? c.order[head * g.cap + first + t.group] : (ring.head_slot + t.group) % g.cap;
     const int tile = block - t.group * g.nb;
     constexpr int ELT = 16 / VEC;
     const int64_t tile_index = ((int64_t)head * g.cap + slot) * g.nb + tile;
@@ -71,13 +105,17 @@ __global__ __launch_bounds__(kThreads) void append_generic_kernel(KGeom g, KCach
     }
     finish_pool<VEC>(red, acc, rg, j, lpr, rows_par, active, g.d, g.tt * t.vh * t.vw,
                      c.pooled + tile_index * g.d);
+    if (threadIdx.x == 0) c.v_clamped[tile_index] = 0;     // this layout stores V as given
+    ring_leave(c, g, ring, n_groups, fresh);
 }
 
-// bf16 bit pattern -> IEEE half bit pattern, round to nearest even, saturating (NaN stays NaN)
-__device__ inline uint32_t bf16_bits_to_half_bits(uint32_t b) {
+// bf16 bit pattern -> IEEE half bit pattern, round to nearest even, saturating (NaN stays NaN);
+// clamped counts the values that did not fit (|v| >= 65536 in bf16, infinities included)
+__device__ inline uint32_t bf16_bits_to_half_bits(uint32_t b, int &clamped) {
     float f = __uint_as_float(b << 16);
     f = fminf(fmaxf(f, -65504.f), 65504.f);          // fmin/fmax return the non-NaN operand: map NaN below
     if ((b & 0x7fffu) > 0x7f80u) return 0x7e00u;      // NaN
+    clamped += (b & 0x7fffu) >= 0x4780u;              // 0x4780 = 65536, the smallest bf16 magnitude above 65504
     const _Float16 h = (_Float16)f;
     return (uint32_t)__builtin_bit_cast(unsigned short, h);
 }
@@ -86,72 +124,102 @@ __device__ inline uint32_t bf16_bits_to_half_bits(uint32_t b) {
 // Cache append, matrix-core tile image (bf16, d = 128, 128 tokens per tile).  Each tile is
 // 128 rows of 256 bytes whose 16-byte chunk j sits at chunk position j ^ (row & 15), so the
 // attention kernel can copy a tile into LDS byte for byte and read matrix operands without
-// bank conflicts.  K rows are tokens (bf16 as given); V is transposed through LDS so that its
-// rows are channels and its columns tokens, and is stored as IEEE half: every bf16 value with
+// bank conflicts.  K rows are tokens (bf16 as given); V is stored transposed, rows = channels and
+// columns = tokens, and as IEEE half: every bf16 value with
 // magnitude in [2^-14, 65504] converts exactly (8 significant bits into 11), smaller ones round
 // to half subnormals (absolute error < 2^-25), larger ones saturate to +-65504.  Half is what the
-// second matrix product runs in, because softmax probabilities need mantissa, not range.
-//                                                                    grid (n_groups*nb, heads)
-constexpr int kVPitchWords = 65;   // LDS pitch of a staged V token row (128 bf16 = 64 words, +1)
-
-__global__ __launch_bounds__(kThreads) void append_mfma_kernel(KGeom g, KCache c, const char *k, const char *v,
-                                                               int64_t st, int64_t sh, int first) {
+// second matrix product runs in, because softmax probabilities need mantissa, not range.  The number of
+// clamped values of the block is stored beside the tile (v_clamped) so that a caller can tell.
+//
+// K: thread (token row rg, chunk j) moves 16-byte chunks, 16 lanes per 256-byte token row, in and out.
+// V: thread (token chunk vc, channel group vj) loads an 8-token x 8-channel square (8 x 16 bytes),
+// transposes it in registers and stores 8 chunks of the transposed image; vc is the fast lane index, so
+// 16 lanes complete one 256-byte row of the image per store.  All 16 loads of a thread are requested before
+// anything is stored.                                                grid n_groups*nb*heads
+__global__ __launch_bounds__(kThreads) void append_mfma_kernel(KGeom g, KCache c, const char *__restrict__ k,
+                                                               const char *__restrict__ v,
+                                                               int64_t st, int64_t sh, int first, int n_groups, bool fresh) {
     __shared__ float red[16 * 128];
-    __shared__ uint32_t vs[128 * kVPitchWords];
-    const int block = blockIdx.x, head = blockIdx.y;
+    __shared__ int n_clamped, ring_word;
+    const int block = blockIdx.x / g.heads, head = blockIdx.x - block * g.heads;
     const TileRef t = tile_ref(g, block);
-    const int slot = c.order ? c.order[head * g.cap + first + t.group] : (first + t.group) % g.cap;
+    const int rg = threadIdx.x >> 4, j = threadIdx.x & 15;     // K: 16 token rows in flight, 16 chunks per row
+    const int vc = threadIdx.x & 15, vj = threadIdx.x >> 4;    // V: tokens 8vc..8vc+7, channels 8vj..8vj+7
+    const bool use_ring = !c.order && !fresh;
+    if (threadIdx.x == 0) {
+        n_clamped = 0;
+        if (use_ring) ring_word = c.ring[0];
+    }
+    uint4 uk[8], uv[8];
+#pragma unroll
+    for (int it = 0; it < 8; ++it) {
+        int ft, r, cc;
+        uk[it] = make_uint4(0, 0, 0, 0);
+        if (block_token(g, rg + 16 * it, t.vh, t.vw, ft, r, cc)) {
+            const int64_t token = raster_token(g, t.group, ft, t.by * g.th + r, t.bx * g.tw + cc);
+            uk[it] = *(const uint4 *)(k + (token * st + (int64_t)head * sh + j * 8) * 2);
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        int ft, r, cc;
+        uv[i] = make_uint4(0, 0, 0, 0);
+        if (block_token(g, 8 * vc + i, t.vh, t.vw, ft, r, cc)) {
+            const int64_t token = raster_token(g, t.group, ft, t.by * g.th + r, t.bx * g.tw + cc);
+            uv[i] = *(const uint4 *)(v + (token * st + (int64_t)head * sh + vj * 8) * 2);
+        }
+    }
+    __syncthreads();                                   // ring_word and n_clamped are set
+    RingPos ring = {use_ring ? ring_word : 0, -1};
+    if (use_ring && threadIdx.x == 0) ring.ticket = atomicAdd(&c.ring[1], 1);      // looked at in ring_leave
+    const int slot = c.order ? c.order[head * g.cap + first + t.group] : (ring.head_slot + t.group) % g.cap;
     const int tile = block - t.group * g.nb;
     const int64_t tile_index = ((int64_t)head * g.cap + slot) * g.nb + tile;
     char *kt = (char *)c.k + tile_index * (128 * 256);
     char *vt = (char *)c.v + tile_index * (128 * 256);
-    const int rg = threadIdx.x >> 4, j = threadIdx.x & 15;   // 16 token rows in flight, 16 chunks per row
+
     float acc[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) acc[e] = 0.f;
 #pragma unroll
     for (int it = 0; it < 8; ++it) {
         const int tok = rg + 16 * it;
-        int ft, r, cc;
-        uint4 uk = make_uint4(0, 0, 0, 0), uv = uk;
-        if (block_token(g, tok, t.vh, t.vw, ft, r, cc)) {
-            const int64_t token = raster_token(g, t.group, ft, t.by * g.th + r, t.bx * g.tw + cc);
-            const int64_t off = (token * st + (int64_t)head * sh + j * 8) * 2;
-            uk = *(const uint4 *)(k + off);
-            uv = *(const uint4 *)(v + off);
-            float f[8];
-            Unpack<8>::to_float(uk, f);
+        float f[8];
+        Unpack<8>::to_float(uk[it], f);                // zeros for padding add nothing
 #pragma unroll
-            for (int e = 0; e < 8; ++e) acc[e] += f[e];
-        }
-        *(uint4 *)(kt + tok * 256 + ((j ^ (tok & 15)) << 4)) = uk;
-        uint32_t *row = vs + tok * kVPitchWords + j * 4;
-        row[0] = uv.x; row[1] = uv.y; row[2] = uv.z; row[3] = uv.w;
+        for (int e = 0; e < 8; ++e) acc[e] += f[e];
+        *(uint4 *)(kt + tok * 256 + ((j ^ (tok & 15)) << 4)) = uk[it];
     }
-    __syncthreads();
-    // transposed write-out: this lane produces the 16-byte piece at (channel dd, chunk position pos)
-    const unsigned short *vh = (const unsigned short *)vs;
+    // V: channel e of this thread's eight tokens -> one 16-byte chunk of row 8vj+e, at chunk position vc ^ (row & 15)
+    int clamped = 0;
 #pragma unroll
-    for (int it = 0; it < 8; ++it) {
-        const int dd = rg + 16 * it, pos = j;
-        const int chunk = pos ^ (dd & 15);           // tokens 8*chunk .. 8*chunk+7
+    for (int e = 0; e < 8; ++e) {
+        const int dd = vj * 8 + e;
         uint32_t w[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const uint32_t lo = vh[(8 * chunk + 2 * i) * (2 * kVPitchWords) + dd];
-            const uint32_t hi = vh[(8 * chunk + 2 * i + 1) * (2 * kVPitchWords) + dd];
-            w[i] = bf16_bits_to_half_bits(lo) | (bf16_bits_to_half_bits(hi) << 16);
+            const uint4 &a = uv[2 * i], &b = uv[2 * i + 1];
+            const uint32_t wa = e < 2 ? a.x : e < 4 ? a.y : e < 6 ? a.z : a.w;
+            const uint32_t wb = e < 2 ? b.x : e < 4 ? b.y : e < 6 ? b.z : b.w;
+            const uint32_t lo = (e & 1) ? wa >> 16 : wa & 0xffffu, hi = (e & 1) ? wb >> 16 : wb & 0xffffu;
+            w[i] = bf16_bits_to_half_bits(lo, clamped) | (bf16_bits_to_half_bits(hi, clamped) << 16);
         }
-        *(uint4 *)(vt + dd * 256 + (pos << 4)) = make_uint4(w[0], w[1], w[2], w[3]);
+        *(uint4 *)(vt + dd * 256 + ((vc ^ (dd & 15)) << 4)) = make_uint4(w[0], w[1], w[2], w[3]);
     }
-    finish_pool<8>(red, acc, rg, j, 16, 16, true, 128, g.tt * t.vh * t.vw, c.pooled + tile_index * 128);
+    if (__ballot(clamped != 0)) {                      // rare: one LDS atomic per wavefront that saw any
+        for (int off = 32; off > 0; off >>= 1) clamped += __shfl_xor(clamped, off);
+        if ((threadIdx.x & 63) == 0) atomicAdd(&n_clamped, clamped);
+    }
+    finish_pool<8>(red, acc, rg, j, 16, 16, true, 128, g.tt * t.vh * t.vw, c.pooled + tile_index * 128);   // holds a barrier
+    if (threadIdx.x == 0) c.v_clamped[tile_index] = (uint32_t)n_clamped;
+    ring_leave(c, g, ring, n_groups, fresh);
 }
 
 } // namespace
 
 hipError_t launch_pool(const KGeom &g, const void *x, int64_t stride_tok, int64_t stride_head,
                        int n_groups, float *pooled, hipStream_t stream) {
-    dim3 grid(n_groups * g.nb, g.heads);
+    dim3 grid(n_groups * g.nb * g.heads);
     if (g.bf16)
         pool_kernel<8><<<grid, kThreads, 0, stream>>>(g, (const char *)x, stride_tok, stride_head, n_groups * g.nb, pooled);
     else
@@ -160,15 +228,15 @@ hipError_t launch_pool(const KGeom &g, const void *x, int64_t stride_tok, int64_
 }
 
 hipError_t launch_append(const KGeom &g, const KCache &c, const void *k, const void *v,
-                         int64_t stride_tok, int64_t stride_head, int n_groups, int first,
+                         int64_t stride_tok, int64_t stride_head, int n_groups, int first, bool fresh,
                          hipStream_t stream) {
-    dim3 grid(n_groups * g.nb, g.heads);
+    dim3 grid(n_groups * g.nb * g.heads);
     if (c.mfma_layout)
-        append_mfma_kernel<<<grid, kThreads, 0, stream>>>(g, c, (const char *)k, (const char *)v, stride_tok, stride_head, first);
+        append_mfma_kernel<<<grid, kThreads, 0, stream>>>(g, c, (const char *)k, (const char *)v, stride_tok, stride_head, first, n_groups, fresh);
     else if (g.bf16)
-        append_generic_kernel<8><<<grid, kThreads, 0, stream>>>(g, c, (const char *)k, (const char *)v, stride_tok, stride_head, first);
+        append_generic_kernel<8><<<grid, kThreads, 0, stream>>>(g, c, (const char *)k, (const char *)v, stride_tok, stride_head, first, n_groups, fresh);
     else
-        append_generic_kernel<4><<<grid, kThreads, 0, stream>>>(g, c, (const char *)k, (const char *)v, stride_tok, stride_head, first);
+        append_generic_kernel<4><<<grid, kThreads, 0, stream>>>(g, c, (const char *)k, (const char *)v, stride_tok, stride_head, first, n_groups, fresh);
     return hipGetLastError();
 }
 

@@ -37,7 +37,8 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(KGeom g, KCache c, 
     extern __shared__ float smem[];
     float *qs = smem;                                  // [d] pooled query of this row
     uint32_t *keys = (uint32_t *)(smem + g.d);         // [n] ordered keys of the admissible blocks (after pooling's partial sums)
-    const int qb = blockIdx.x, head = blockIdx.y, tid = threadIdx.x, lane = tid & 63;
+    const int qb = blockIdx.x / g.heads, head = blockIdx.x - qb * g.heads;     // head-fastest, like the pooling kernels
+    const int tid = threadIdx.x, lane = tid & 63;
     const int n_qb = g.q_groups * g.nb;
     const int tile = qb % g.nb, by = tile / g.tx, bx = tile - by * g.tx;
     int y0, y1, x0, x1;
@@ -46,6 +47,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(KGeom g, KCache c, 
     const int wx = x1 - x0, nwin = (y1 - y0) * wx;
     const int n = c.valid * nwin;                      // admissible key blocks, in ascending id order
     const int64_t row = (int64_t)head * n_qb + qb;
+    const int start = ring_start(c, g);                // requested here, needed after the pooling
 
     if constexpr (VEC == 0) {
         for (int i = tid; i < g.d; i += kSelThreads) qs[i] = pooled_q[row * g.d + i];
@@ -91,7 +93,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(KGeom g, KCache c, 
             if (ci < n) {
                 int f;
                 const int t = tile_of(ci, f);
-                const int slot = cache_slot(c, g, head, f);
+                const int slot = cache_slot(c, g, start, head, f);
                 const float4 *kr = (const float4 *)(c.pooled + (((int64_t)head * g.cap + slot) * g.nb + t) * g.d);
                 for (int e0 = part; e0 < n4; e0 += 4 * 16) {
                     float4 kk[16];
@@ -199,7 +201,7 @@ int max_candidates(const KGeom &g, int valid_groups) {
 
 hipError_t launch_select(const KGeom &g, const KCache &c, const float *pooled_q,
                          int32_t *sel_idx, int32_t *sel_cnt, float *gap, int max_cand, hipStream_t stream) {
-    dim3 grid(g.q_groups * g.nb, g.heads);
+    dim3 grid(g.q_groups * g.nb * g.heads);
     const size_t lds = (size_t)(g.d + max_cand) * sizeof(float);
     select_kernel<0><<<grid, kSelThreads, lds, stream>>>(g, c, pooled_q, nullptr, 0, 0, nullptr, sel_idx, sel_cnt, gap);
     return hipGetLastError();
@@ -207,7 +209,7 @@ hipError_t launch_select(const KGeom &g, const KCache &c, const float *pooled_q,
 
 hipError_t launch_pool_select(const KGeom &g, const KCache &c, const void *q, int64_t q_st, int64_t q_sh, float *pooled_q,
                               int32_t *sel_idx, int32_t *sel_cnt, float *gap, int max_cand, hipStream_t stream) {
-    dim3 grid(g.q_groups * g.nb, g.heads);
+    dim3 grid(g.q_groups * g.nb * g.heads);
     const int vec = g.bf16 ? 8 : 4;
     const size_t lds = (size_t)(g.d + (max_cand > kSelThreads * vec ? max_cand : kSelThreads * vec)) * sizeof(float);
     if (g.bf16)

@@ -15,6 +15,11 @@ from paper_2510_12747_amd import workloads as wl
 NEAR_TIE = 1e-3          # selection may differ from the oracle only where its score gap is below this
 OUT_MAX_ABS = 1e-2       # output tolerances from the benchmark definition (unit-variance V)
 OUT_MEAN_ABS = 1e-3
+IMPORTANCE_RTOL = 2e-4   # group importance: fp32 sums of up to a few thousand softmax weights against fp64
+# An eviction decision may differ from the oracle's only among groups whose oracle importances lie within this
+# relative band: two values that each carry the relative error asserted above can swap order only if they are
+# closer than 2 * IMPORTANCE_RTOL; the band leaves a little room on top of that.
+EVICT_NEAR_TIE_REL = 5e-4
 
 
 def say(msg: str) -> None:
@@ -71,9 +76,12 @@ class StepResult:
     rows_checked: int
 
 
-def check_selection(sel_idx, sel_cnt, o_idx, o_cnt, o_gap, og, kv_frames):
+def check_selection(sel_idx, sel_cnt, o_idx, o_cnt, o_gap, og, kv_frames, S):
     """Bit-exact selection except rows whose oracle gap is below NEAR_TIE; every GPU row must
-    still be a valid selection (ascending, unique, admissible, right count, -1 padded)."""
+    still be a valid selection (ascending, unique, admissible, right count, -1 padded), and on a
+    row that differs the exchange must be one the oracle's own fp64 scores S allow: every block
+    the GPU kept scores at least S_(k) - NEAR_TIE and every block of the oracle's set that the
+    GPU left out scores at most S_(k) + NEAR_TIE, S_(k) being the oracle's weakest kept score."""
     sel_idx, sel_cnt = sel_idx.cpu().numpy(), sel_cnt.cpu().numpy()
     np.testing.assert_array_equal(sel_cnt, o_cnt)
     diff = (sel_idx != o_idx).any(axis=-1)
@@ -81,21 +89,39 @@ def check_selection(sel_idx, sel_cnt, o_idx, o_cnt, o_gap, og, kv_frames):
     bad = diff & ~near
     assert not bad.any(), f"{bad.sum()} rows differ from the oracle with gap >= {NEAR_TIE}: first {np.argwhere(bad)[:5]}"
     for h, qb in np.argwhere(diff):
-        m = sel_cnt[h, qb]
-        kept = sel_idx[h, qb, :m]
-        assert (np.diff(kept) > 0).all() and (sel_idx[h, qb, m:] == -1).all()
-        assert all(oracle.allowed(int(qb), int(kb), og) for kb in kept) and kept.max() < kv_frames // og.tile_t * og.nb
+        assert_valid_near_tie_row(sel_idx[h, qb], int(sel_cnt[h, qb]), o_idx[h, qb], S[h, qb], int(qb), og, kv_frames)
     return sel_idx, sel_cnt, int(diff.sum()), int(near.sum())
 
 
+def assert_valid_near_tie_row(got_ids, m, oracle_ids, s_row, qb, og, kv_frames):
+    """A row whose kept set differs from the oracle's: structure, admissibility, and the score bounds
+    that make it an exchange among near-tied blocks (s_row = the oracle's fp64 scores of the row)."""
+    kept = got_ids[:m]
+    assert (np.diff(kept) > 0).all() and (got_ids[m:] == -1).all()
+    assert kept.min() >= 0 and kept.max() < kv_frames // og.tile_t * og.nb
+    assert all(oracle.allowed(qb, int(kb), og) for kb in kept)
+    want = oracle_ids[:m]
+    s_k = s_row[want].min()                                # the oracle's weakest kept score
+    extra = np.setdiff1d(kept, want)                       # kept by the GPU only
+    lost = np.setdiff1d(want, kept)                        # kept by the oracle only
+    assert len(extra) == len(lost) > 0
+    assert (s_row[extra] >= s_k - NEAR_TIE).all(), f"row {qb}: kept block scores {s_row[extra]} below S_k {s_k} - {NEAR_TIE}"
+    assert (s_row[lost] <= s_k + NEAR_TIE).all(), f"row {qb}: dropped block scores {s_row[lost]} above S_k {s_k} + {NEAR_TIE}"
+
+
 def check_outputs(o_gpu: torch.Tensor, q, K, V, og, kv_frames, sel_idx, sel_cnt, rows, scale=0.0,
-                  max_abs=OUT_MAX_ABS, mean_abs=OUT_MEAN_ABS, bf16_relative=False):
+                  max_abs=OUT_MAX_ABS, mean_abs=OUT_MEAN_ABS, bf16_relative=False, large_v=False):
     """Compares against the oracle's attention on the SAME selection (the GPU's, which equals the
     oracle's except on reported near-tie rows).
 
-    bf16_relative: for shapes where a row attends to a handful of keys (tiny clipped blocks) |o| reaches
-    4 and more and the rounding of O to bf16 alone (half an ulp = up to 2^-8 |o|) exceeds max_abs; the
-    bound is then 2^-8 |o| + 2e-3 per element (rounding of the result + everything inside the kernel)."""
+    bf16_relative: for shapes where a row attends to a handful of keys (tiny clipped blocks, sharp softmax rows)
+    |o| reaches 4 and more and the rounding of O to bf16 alone (half an ulp = up to 2^-8 |o|) exceeds max_abs;
+    the bound is then 2^-8 |o| + 2e-3 per element (rounding of the result + everything inside the kernel), and
+    the mean bound grows by the mean rounding error of the result, a quarter ulp <= 2^-9 |o|.
+
+    large_v (with bf16_relative): V far from unit variance.  What happens inside the kernel then scales with the
+    values averaged, not with the result: probabilities enter the second product rounded to half (relative 2^-11
+    each), so the per-element bound gains 2^-10 * sum_j p_j |v_j|, the attention of |V| taken from the oracle."""
     want = oracle.attend(q, K, V, og, kv_frames, sel_idx, sel_cnt, scale=scale, rows=rows)
     got = o_gpu.float().cpu().numpy().astype(np.float64)
     done = ~np.isnan(want)
@@ -104,13 +130,39 @@ def check_outputs(o_gpu: torch.Tensor, q, K, V, og, kv_frames, sel_idx, sel_cnt,
     assert np.isfinite(got[done]).all()
     if bf16_relative:
         bound = 2.0 ** -8 * np.abs(want[done]) + 2e-3
+        if large_v:
+            bound += 2.0 ** -10 * oracle.attend(q, K, np.abs(V), og, kv_frames, sel_idx, sel_cnt, scale=scale, rows=rows)[done]
         worst = int(np.argmax(err - bound))
         assert (err <= bound).all(), f"error {err[worst]:.3e} at |o| = {abs(want[done][worst]):.3f} exceeds {bound[worst]:.3e}"
+        mean_bound = mean_abs + 2.0 ** -9 * np.abs(want[done]).mean() + (bound.mean() if large_v else 0.0)
+        assert err.mean() <= mean_bound, f"mean-abs {err.mean():.3e} > {mean_bound:.3e}"
         return float(err.max()), float(err.mean())
     worst = int(np.argmax(err))
     assert err.max() <= max_abs, f"max-abs {err.max():.3e} > {max_abs} (at |o| = {abs(want[done][worst]):.3f})"
     assert err.mean() <= mean_abs, f"mean-abs {err.mean():.3e} > {mean_abs}"
     return float(err.max()), float(err.mean())
+
+
+def check_eviction(got, own, imp, uniform, rel=EVICT_NEAR_TIE_REL) -> int:
+    """got / own: per head, the positions (temporal order) dropped by the implementation under test / by the
+    oracle's model; imp[heads][groups]: the oracle's importances the decision was taken on.  The two may differ
+    only by an exchange among groups whose oracle importances lie within the relative band `rel` (equal
+    importances, e.g. a cache that was never scored, admit no exchange: the older group goes).  Returns the
+    number of heads decided differently."""
+    if uniform:
+        assert all(g == got[0] for g in got), f"uniform policy: heads decided differently: {got}"
+    differing = 0
+    for h, (a, b) in enumerate(zip(got, own)):
+        assert len(a) == len(b) and len(set(a)) == len(a), f"head {h}: dropped {a}, the oracle drops {b}"
+        if sorted(a) == sorted(b):
+            continue
+        differing += 1
+        swapped = sorted(set(a) ^ set(b))
+        lo, hi = imp[h, swapped].min(), imp[h, swapped].max()
+        assert hi > lo, f"head {h}: dropped {a} instead of {b} although the groups tie exactly (older goes first)"
+        assert hi - lo <= rel * hi, (f"head {h}: dropped {a}, the oracle drops {b}; importances of the exchanged "
+                                     f"groups {imp[h, swapped]} are further apart than {rel} relative")
+    return differing
 
 
 class Pipeline:
@@ -135,8 +187,24 @@ class Pipeline:
         if q is None:
             q, k, v = self.stream.next()
         w = self.w
-        self.model.append(k, v, w.q_frames)
-        B.lcsa_kv_cache_append(self.cache, to_device(k, w.dtype, self.layout), to_device(v, w.dtype, self.layout), w.q_frames)
+        kd, vd = to_device(k, w.dtype, self.layout), to_device(v, w.dtype, self.layout)
+        if isinstance(self.model, oracle.ImportanceCache):
+            # The library decides on the device which groups leave.  Its decision is read back from the slot
+            # table, checked against what the oracle's fp64 importances allow, and the model then drops the
+            # same groups, so that a near-tie decided the other way does not end the comparison.
+            n = self.model.valid_frames // self.g.tile_t
+            before = B.lcsa_cache_order(self.cache).cpu().numpy().copy()
+            B.lcsa_kv_cache_append(self.cache, kd, vd, w.q_frames)
+            after = B.lcsa_cache_order(self.cache).cpu().numpy()
+            own = self.model.victims(w.q_frames)
+            m = n - len(own[0])
+            got = [[i for i in range(n) if before[h, i] not in set(after[h, :m].tolist())] for h in range(self.g.heads)]
+            self.near_tie_evictions = getattr(self, "near_tie_evictions", 0) + check_eviction(
+                got, own, self.model.importances(), self.eviction == B.LCSA_EVICT_IMPORTANCE_UNIFORM)
+            self.model.append(k, v, w.q_frames, victims=got)
+        else:
+            self.model.append(k, v, w.q_frames)
+            B.lcsa_kv_cache_append(self.cache, kd, vd, w.q_frames)
         assert B.lcsa_cache_valid_frames(self.cache) == self.model.valid_frames
         self.chunk += 1
         return q, to_device(q, w.dtype, self.layout)
@@ -160,9 +228,9 @@ class Pipeline:
             n = self.model.valid_frames // tt
             assert all(len(set(order[h, :n])) == n and order[h, :n].max() < self.g.cache_frames // tt for h in range(self.g.heads))
 
-    def score_groups(self, q, qd, rtol=2e-4):
-        """lcsa_block_importance against the oracle's importance of the visible groups; the oracle's
-        values then drive the model's next eviction.  Returns the oracle's importance."""
+    def score_groups(self, q, qd, rtol=IMPORTANCE_RTOL):
+        """lcsa_block_importance against the oracle's importance of the visible groups; the oracle's own
+        values drive the model's next eviction.  Returns the oracle's importance."""
         pq = B.lcsa_pool_blocks(self.g, qd, self.g.q_frames)
         got = B.lcsa_block_importance(self.g, pq, self.cache).cpu().numpy()
         kvf = self.model.valid_frames
@@ -174,26 +242,7 @@ class Pipeline:
         assert (got[:, n:] == 0).all()
         np.testing.assert_allclose(got.sum(axis=1), self.g.n_qb, rtol=1e-4)     # one unit of attention per query block
         if isinstance(self.model, oracle.ImportanceCache):
-            # Which groups go at the next append is decided by these numbers.  Where the oracle's own decision
-            # hinges on a near-tie (relative margin below 2e-3, far above the fp32 error checked above) the model
-            # follows the kernel's numbers, as for near-ties of the block selection; such cases are reported.
-            cap, n_new = self.g.cache_frames // self.g.tile_t, self.g.q_frames // self.g.tile_t
-            n_evict = max(0, n + n_new - cap)
-            feed, near = want.copy(), 0
-            if n_evict:
-                uniform = self.eviction == B.LCSA_EVICT_IMPORTANCE_UNIFORM
-                srt = np.sort(want.sum(axis=0, keepdims=True) if uniform else want, axis=1)
-                tie = (srt[:, n_evict] - srt[:, n_evict - 1]) < 2e-3 * srt[:, n_evict]
-                near = int(tie.sum())
-                if uniform and tie[0]:
-                    acc = np.zeros(n, np.float32)
-                    for h in range(self.g.heads):                # the kernel's own summation order
-                        acc = acc + got[h, :n]
-                    feed = np.broadcast_to(acc.astype(np.float64), want.shape).copy()
-                elif not uniform:
-                    feed[tie] = got[tie][:, :n]
-            self.model.set_importance(feed)
-            self.near_tie_evictions = getattr(self, "near_tie_evictions", 0) + near
+            self.model.set_importance(want)
         return want
 
     def step(self, q, qd, rows=None, g=None, og=None, scale=0.0, max_abs=OUT_MAX_ABS, mean_abs=OUT_MEAN_ABS,
@@ -215,7 +264,7 @@ class Pipeline:
         np.testing.assert_allclose(pq.cpu().numpy(), o_pq, rtol=0, atol=2e-5)
         S = oracle.scores(o_pq, oracle.pool(K, og, kvf))
         o_idx, o_cnt, o_gap = oracle.select(S, og, kvf)
-        s_idx, s_cnt, n_diff, n_near = check_selection(sel_idx, sel_cnt, o_idx, o_cnt, o_gap, og, kvf)
+        s_idx, s_cnt, n_diff, n_near = check_selection(sel_idx, sel_cnt, o_idx, o_cnt, o_gap, og, kvf, S)
         ggap = gap.cpu().numpy()
         fin = np.isfinite(o_gap)
         assert (np.isinf(ggap) == ~fin).all()

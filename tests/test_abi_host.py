@@ -40,9 +40,11 @@ def up256(n):
     return -(-n // 256) * 256
 
 
-def eviction_state_bytes(heads, groups, n_qb):
-    """visible-group -> slot table, importance per group, per-row scratch of the importance kernel"""
-    return up256(heads * groups * 4) + up256(heads * groups * 4) + up256(heads * n_qb * groups * 4)
+def eviction_state_bytes(heads, groups, n_qb, nb):
+    """visible-group -> slot table, importance per group, per-row scratch of the importance kernel, the ring
+    words of the sliding window, clamped-V counts per tile"""
+    return up256(heads * groups * 4) + up256(heads * groups * 4) + up256(heads * n_qb * groups * 4) + 256 \
+        + up256(heads * groups * nb * 4)
 
 
 def test_cache_bytes_formula():
@@ -50,14 +52,14 @@ def test_cache_bytes_formula():
     nb = 6 * 6
     tiles = 12 * 6 * nb
     assert g.nb == nb
-    assert B.lcsa_cache_device_bytes(g) == 2 * tiles * 128 * 128 * 2 + tiles * 128 * 4 + eviction_state_bytes(12, 6, 72)
+    assert B.lcsa_cache_device_bytes(g) == 2 * tiles * 128 * 128 * 2 + tiles * 128 * 4 + eviction_state_bytes(12, 6, 72, 36)
     tiny = B.Geom(1, 32, 6, 8, 4, 4, 2, 4, 4, 4, 4, dtype=B.LCSA_F32)
-    assert B.lcsa_cache_device_bytes(tiny) == 2 * (16 * 16 * 32 * 4) + 16 * 32 * 4 + eviction_state_bytes(1, 4, 8)
+    assert B.lcsa_cache_device_bytes(tiny) == 2 * (16 * 16 * 32 * 4) + 16 * 32 * 4 + eviction_state_bytes(1, 4, 8, 4)
     # (2,8,8) blocks on the paper grid: 66 blocks per frame pair, 3 pairs in the ring, 128 tokens per block
     paper288 = B.Geom(**{**PAPER, "tile_w": 8, "tile_t": 2})
     assert paper288.nb == 66 and paper288.n_qb == 66
     assert B.lcsa_cache_device_bytes(paper288) == 2 * (12 * 3 * 66) * 128 * 128 * 2 + (12 * 3 * 66) * 128 * 4 \
-        + eviction_state_bytes(12, 3, 66)
+        + eviction_state_bytes(12, 3, 66, 66)
 
 
 @pytest.mark.parametrize("field,value", [

@@ -60,18 +60,20 @@ def test_ultra_high_res_sampled_rows():
 
 
 def test_4k_streaming_ring_and_topk_sweep():
-    """1 query frame per chunk, ring of 6 frames: checks while the ring fills, after it wraps,
-    and the top-k sweep {16, 32, 64} (corner tiles have 48 < 64 candidates) on the wrapped state."""
+    """1 query frame per chunk, ring of 6 frames, all 16 chunks of the configuration: checks while the ring fills,
+    after it wraps, at the last chunk (the ring has then gone round twice and a half), and the top-k sweep
+    {16, 32, 64} (corner tiles have 48 < 64 candidates) on that last state."""
     w = wl.WORKLOADS["4k"]
     g, og = geoms(w)
     p = Pipeline(w)
-    for chunk in range(8):
+    for chunk in range(w.n_chunks):
         q, qd = p.feed()
-        if chunk in (0, 2, 7):
+        if chunk in (0, 2, 7, 11, 15):
             say(f"4k chunk {chunk}: {p.model.valid_frames} visible frames")
             p.check_pooled_k()
             r = p.step(q, qd, rows=sample_rows(og, 24, seed=chunk))
             say(f"  near-tie rows {r.near_tie_rows}, differs {r.sel_mismatch_rows}, max-abs {r.max_abs:.2e}, mean-abs {r.mean_abs:.2e}")
+    assert p.chunk == 16
     for k in (16, 64):
         gk, ogk = geoms(w, topk=k)
         r = p.step(q, qd, rows=sample_rows(ogk, 16, seed=k), g=gk, og=ogk)
@@ -79,9 +81,9 @@ def test_4k_streaming_ring_and_topk_sweep():
 
 
 def test_full_sizes_every_row():
-    """At full size the other tests sample rows; here every output row of one paper-scale layer call and of one
-    4K chunk (ring full) goes through the oracle: 864 + 3060 work items, each placed on a workgroup, a group
-    and an XCD by the launch arithmetic that the benchmark uses."""
+    """At full size the other tests sample rows; here every output row of one paper-scale layer call, of one
+    4K chunk (ring full) and of one ultra-high-res layer call goes through the oracle: 864 + 3060 + 2880 work
+    items, each placed on a workgroup, a group and an XCD by the launch arithmetic that the benchmark uses."""
     p, r = run_primed(wl.WORKLOADS["paper"], layer=3)
     assert r.rows_checked == 12 * 72
     w = wl.WORKLOADS["4k"]
@@ -91,6 +93,9 @@ def test_full_sizes_every_row():
     r = p.step(q, qd)
     assert r.rows_checked == 12 * 255
     say(f"4k all rows: near-tie rows {r.near_tie_rows}, differs {r.sel_mismatch_rows}, max-abs {r.max_abs:.2e}, mean-abs {r.mean_abs:.2e}")
+    del p
+    p, r = run_primed(wl.WORKLOADS["ultra"], layer=1)
+    assert r.rows_checked == 12 * 240
 
 
 # ---- edge cases and variants -------------------------------------------------------------------
@@ -165,7 +170,7 @@ def test_uneven_appends_wrap_the_ring():
     torch.cuda.synchronize()
     S = oracle.scores(oracle.pool(q, og, 1), oracle.pool(K, og, 4))
     o_idx, o_cnt, o_gap = oracle.select(S, og, 4)
-    s_idx, s_cnt, _, _ = check_selection(sel_idx, sel_cnt, o_idx, o_cnt, o_gap, og, 4)
+    s_idx, s_cnt, _, _ = check_selection(sel_idx, sel_cnt, o_idx, o_cnt, o_gap, og, 4, S)
     check_outputs(o, q, K, V, og, 4, s_idx, s_cnt, None)
     # reset: the cache forgets everything and starts over from slot 0
     B.lcsa_cache_reset(cache)
@@ -366,7 +371,7 @@ def run_eviction_stream(w, policy, pattern, gains, **kw):
         k = k * np.float32(gain)
         q, qd = p.feed(q, wl.round_to_bf16(k) if w.dtype == "bf16" else k, v)
         p.check_pooled_k()
-        r = p.step(q, qd, **tol)
+        r = p.step(q, qd, bf16_relative=w.dtype == "bf16", **tol)
         p.score_groups(q, qd)
         say(f"{w.name} policy {policy} chunk {chunk}: groups per head {p.model.birth_order().tolist()}, "
             f"max-abs {r.max_abs:.2e}")
@@ -375,7 +380,7 @@ def run_eviction_stream(w, policy, pattern, gains, **kw):
 
 
 PATTERN = [0, 1, 0, 0, 1, 0, 1, 1, 0]
-GAINS = [1.0, 0.8, 0.95, 0.9, 0.85, 0.75, 1.0, 0.85, 0.9]      # at most 1: sharper softmax rows would raise |o| and with it the bf16 rounding of O
+GAINS = [1.0, 0.8, 1.25, 0.9, 1.1, 0.75, 1.0, 1.4, 0.9]       # above 1: sharper softmax rows, larger |o| (relative output bound)
 
 
 @pytest.mark.parametrize("policy", [B.LCSA_EVICT_IMPORTANCE_HEADWISE, B.LCSA_EVICT_IMPORTANCE_UNIFORM])
@@ -476,24 +481,21 @@ def test_geometry_sweep_matrix_core_path(case):
 
 # ---- the streaming path inside a captured HIP graph -----------------------------------------------------
 
-def test_streaming_layer_call_replays_from_a_captured_graph():
-    """Under an importance policy the visible-group -> slot table lives on the device, and once the cache is full
-    every layer call has the same arguments: one captured graph of (evict + append, pool, select, attend) can be
-    replayed chunk after chunk.  Unscored, the policy evicts the oldest group, i.e. it is the sliding window.
-    Every replay is compared bit for bit with the same call made eagerly on a twin cache, with eager work and
-    synchronisations between the replays, and with the oracle's sliding-window model."""
+@pytest.mark.parametrize("policy", [B.LCSA_EVICT_SLIDING, B.LCSA_EVICT_IMPORTANCE_HEADWISE])
+def test_streaming_layer_call_replays_from_a_captured_graph(policy):
+    """Where the new frames go is decided on the device (sliding window: a ring position that the append launch
+    advances; importance policy, here unscored and hence oldest-first: the slot table), and once the cache is full
+    every layer call has the same arguments: one captured graph of (append, pool, select, attend) can be replayed
+    chunk after chunk.  Every replay is compared bit for bit with the same call made eagerly on a twin cache,
+    with eager work and synchronisations between the replays, and with the oracle's sliding-window model."""
     w = wl.with_overrides(wl.WORKLOADS["small"], name="graph-small", heads=2, q_frames=1, cache_frames=4)
     g, og = geoms(w)
     stream = wl.ChunkStream(w, 0)
-    chunks = [stream.next() for _ in range(9)]
+    chunks = [stream.next() for _ in range(10)]
     model = oracle.SlidingWindowCache(w.cache_frames)
     caches = [B.lcsa_cache_init(g), B.lcsa_cache_init(g)]
     for c in caches:
-        B.lcsa_cache_set_eviction(c, B.LCSA_EVICT_IMPORTANCE_HEADWISE)
-    for q, k, v in chunks[:4]:                                  # fill both caches eagerly
-        model.append(k, v, 1)
-        for c in caches:
-            B.lcsa_kv_cache_append(c, to_device(k, "bf16"), to_device(v, "bf16"), 1)
+        B.lcsa_cache_set_eviction(c, policy)
     qs, ks, vs = (torch.empty_like(to_device(x, "bf16")) for x in chunks[0])
     outs = [dict(pq=torch.empty(g.heads, g.n_qb, g.head_dim, dtype=torch.float32, device="cuda"),
                  si=torch.empty(g.heads, g.n_qb, g.topk, dtype=torch.int32, device="cuda"),
@@ -506,11 +508,29 @@ def test_streaming_layer_call_replays_from_a_captured_graph():
         B.lcsa_select_blocks(g, out["pq"], cache, out["si"], out["sc"], want_gap=False)
         B.lcsa_sparse_attn_fwd(g, qs, cache, out["si"], out["sc"], out["o"])
 
+    for q, k, v in chunks[:3]:                                  # not full yet: 3 of 4 frames
+        model.append(k, v, 1)
+        for c in caches:
+            B.lcsa_kv_cache_append(c, to_device(k, "bf16"), to_device(v, "bf16"), 1)
+    # a capture taken now would bake the number of visible frames into its launches: refused, nothing recorded
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    refused = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(refused, stream=side):
+        with pytest.raises(B.LcsaError, match="unsupported"):
+            B.lcsa_kv_cache_append(caches[1], ks, vs, 1)
+        outs[1]["sc"].zero_()                                   # a graph needs at least one node
+    assert B.lcsa_cache_valid_frames(caches[1]) == 3
+    q, k, v = chunks[3]                                         # fill both caches eagerly
+    model.append(k, v, 1)
+    for c in caches:
+        B.lcsa_kv_cache_append(c, to_device(k, "bf16"), to_device(v, "bf16"), 1)
+
     torch.cuda.synchronize()
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.graph(graph):
         layer_call(caches[1], outs[1])                          # recorded, not run
-    for n, (q, k, v) in enumerate(chunks[4:]):
+    for n, (q, k, v) in enumerate(chunks[4:]):                  # 6 replays: the ring of 4 goes round one and a half times
         say(f"graph replay {n}")
         for dst, src in ((qs, q), (ks, k), (vs, v)):
             dst.copy_(to_device(src, "bf16"))
@@ -521,9 +541,79 @@ def test_streaming_layer_call_replays_from_a_captured_graph():
         torch.cuda.synchronize()
         for key in ("si", "sc", "o", "pq"):
             assert torch.equal(outs[0][key], outs[1][key]), f"replay {n}: {key} differs from the eager call"
-        assert torch.equal(B.lcsa_cache_order(caches[0]), B.lcsa_cache_order(caches[1]))
+        if policy != B.LCSA_EVICT_SLIDING:
+            assert torch.equal(B.lcsa_cache_order(caches[0]), B.lcsa_cache_order(caches[1]))
+        assert torch.equal(B.lcsa_cache_pooled_k(caches[0]), B.lcsa_cache_pooled_k(caches[1]))
         K, V = model.visible()
         S = oracle.scores(oracle.pool(q, og, 1), oracle.pool(K, og, 4))
         o_idx, o_cnt, o_gap = oracle.select(S, og, 4)
-        s_idx, s_cnt, _, _ = check_selection(outs[1]["si"], outs[1]["sc"], o_idx, o_cnt, o_gap, og, 4)
+        s_idx, s_cnt, _, _ = check_selection(outs[1]["si"], outs[1]["sc"], o_idx, o_cnt, o_gap, og, 4, S)
         check_outputs(outs[1]["o"], q, K, V, og, 4, s_idx, s_cnt, None)
+
+
+# ---- range of V on the matrix-core path (V is stored as IEEE half) --------------------------------------------
+
+def _channel_sign(v):
+    """+1 on even channels, -1 on odd ones, broadcast to v's shape: the planted large values of one channel then
+    share a sign, so that an output never is a small difference of huge terms (whose rounding no bound on
+    |o| could cover)."""
+    return np.broadcast_to(np.where(np.arange(v.shape[-1]) % 2 == 0, 1.0, -1.0).astype(np.float32), v.shape)
+
+
+def _v_range_case(v_edit):
+    """One layer call on the edge grid with V modified by v_edit(V) -> V; returns everything a check needs."""
+    w = wl.with_overrides(SMALL_MFMA, name="v-range", heads=2)
+    g, og = geoms(w)
+    stream = wl.ChunkStream(w, 0)
+    cache = B.lcsa_cache_init(g)
+    model = oracle.SlidingWindowCache(w.cache_frames)
+    for _ in range(3):
+        q, k, v = stream.next()
+        v = wl.round_to_bf16(v_edit(v))
+        model.append(k, v, w.q_frames)
+        B.lcsa_kv_cache_append(cache, to_device(k, "bf16"), to_device(v, "bf16"), w.q_frames)
+    qd = to_device(q, "bf16")
+    sel_idx, sel_cnt, _ = B.lcsa_select_blocks(g, B.lcsa_pool_blocks(g, qd, g.q_frames), cache)
+    o = B.lcsa_sparse_attn_fwd(g, qd, cache, sel_idx, sel_cnt)
+    torch.cuda.synchronize()
+    K, V = model.visible()
+    return g, og, cache, q, K, V, sel_idx.cpu().numpy(), sel_cnt.cpu().numpy(), o
+
+
+def test_v_up_to_the_largest_exact_value_and_tiny_values_match_the_oracle():
+    """|v| = 65280 (the largest bf16 value that half holds) and values below half's subnormal range: the first
+    are stored exactly, the second round to multiples of 2^-24 (absolute error <= 2^-25); nothing is clamped."""
+    rng = np.random.default_rng(31)
+
+    def edit(v):
+        v = v.copy()
+        big = rng.random(v.shape) < 0.002
+        v[big] = (65280.0 * _channel_sign(v))[big]
+        small = rng.random(v.shape) < 0.01
+        v[small] = (rng.choice([1e-8, -3e-8, 2.0 ** -20, 2.0 ** -24, 1e-30], small.sum())).astype(np.float32)
+        return v
+
+    g, og, cache, q, K, V, s_idx, s_cnt, o = _v_range_case(edit)
+    assert (np.abs(V) == 65280.0).sum() > 100
+    assert int(B.lcsa_cache_v_clamped(cache).sum()) == 0
+    mx, mean = check_outputs(o, q, K, V, og, 6, s_idx, s_cnt, None, bf16_relative=True, large_v=True)
+    say(f"V up to 65280: max-abs {mx:.3e} (|o| reaches {np.abs(o.float().cpu().numpy()).max():.0f})")
+
+
+def test_v_beyond_half_range_is_clamped_and_counted():
+    """|v| >= 65536 (and infinities) are stored as +-65504: the output is the attention of eq. (1) on the clamped V,
+    and the per-block counters tell how many values were clamped."""
+    rng = np.random.default_rng(32)
+    planted = []
+
+    def edit(v):
+        v = v.copy()
+        big = rng.random(v.shape) < 0.001
+        v[big] = (rng.choice([65536.0, 1e5, 3e38, np.inf], v.shape).astype(np.float32) * _channel_sign(v))[big]
+        planted.append(int(big.sum()))
+        return v
+
+    g, og, cache, q, K, V, s_idx, s_cnt, o = _v_range_case(edit)
+    assert int(B.lcsa_cache_v_clamped(cache).sum()) == sum(planted) > 0       # all three chunks are still visible
+    mx, mean = check_outputs(o, q, K, np.clip(V, -65504.0, 65504.0), og, 6, s_idx, s_cnt, None, bf16_relative=True, large_v=True)
+    say(f"V clamped: {sum(planted)} values, max-abs {mx:.3e}")
