@@ -159,6 +159,15 @@ int32_t lcsa_cache_eviction(const lcsa_cache *cache);
  * after the chunk's own append, with the pooled queries lcsa_select_blocks was given.
  */
 int32_t lcsa_block_importance(const lcsa_geom *geom, const float *pooled_q, lcsa_cache *cache, float scale, void *stream);
+/*
+ * lcsa_block_importance for callers that cannot allocate or size a workspace (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc): identical results, but the per-row partial sums live
+ * in a static device array inside the library (1 MiB, held on every GPU the library runs on until the process
+ * ends) instead of in the cache's own memory.  Allocates nothing.  Needs heads * n_qb * (cache_frames/tile_t)
+ * <= 262144, else LCSA_EUNSUPPORTED.  Runs on the CURRENT device, to which the stream and all pointers must
+ * belong.  Every call on one GPU uses the same array: calls that overlap on one GPU (different streams) race.
+ */
+int32_t lcsa_block_importance_static(const lcsa_geom *geom, const float *pooled_q, lcsa_cache *cache, float scale, void *stream);
 /* Inspection helpers for tests: the scores above, and under an importance policy the device table
  * int32 [heads][cache_frames/tile_t], visible group (0 = oldest) -> slot (NULL under the sliding window,
  * where lcsa_cache_frame_slot answers on the host). */

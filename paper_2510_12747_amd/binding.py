@@ -103,6 +103,7 @@ def lib():
         L.lcsa_cache_set_eviction.argtypes = [_vp, _i32]
         L.lcsa_cache_eviction.argtypes = [_vp]
         L.lcsa_block_importance.argtypes = [_gp, _vp, _vp, _f32, _vp]
+        L.lcsa_block_importance_static.argtypes = [_gp, _vp, _vp, _f32, _vp]
         L.lcsa_cache_importance_device.argtypes = [_vp]
         L.lcsa_cache_importance_device.restype = _vp
         L.lcsa_cache_order_device.argtypes = [_vp]
@@ -112,7 +113,8 @@ def lib():
         L.lcsa_last_hip_error.restype = ctypes.c_char_p
         for f in ("lcsa_cache_init", "lcsa_cache_reset", "lcsa_cache_valid_frames", "lcsa_cache_frame_slot",
                   "lcsa_kv_cache_append", "lcsa_pool_blocks", "lcsa_select_blocks", "lcsa_sparse_attn_fwd",
-                  "lcsa_pool_select_blocks", "lcsa_cache_set_eviction", "lcsa_cache_eviction", "lcsa_block_importance"):
+                  "lcsa_pool_select_blocks", "lcsa_cache_set_eviction", "lcsa_cache_eviction", "lcsa_block_importance",
+                  "lcsa_block_importance_static"):
             getattr(L, f).restype = _i32
         _lib = L
     return _lib
@@ -206,6 +208,16 @@ def lcsa_block_importance(geom: Geom, pooled_q: torch.Tensor, cache: Cache, scal
     g = geom.c()
     _check(lib().lcsa_block_importance(ctypes.byref(g), pooled_q.data_ptr(), cache.handle, scale, _stream(stream)),
            "lcsa_block_importance")
+    return lcsa_cache_importance(cache)
+
+
+def lcsa_block_importance_static(geom: Geom, pooled_q: torch.Tensor, cache: Cache, scale: float = 0.0, stream=None) -> torch.Tensor:
+    """lcsa_block_importance with the library's static scratch array (allocates nothing)."""
+    assert pooled_q.is_contiguous() and pooled_q.dtype == torch.float32
+    assert pooled_q.shape == (geom.heads, geom.n_qb, geom.head_dim)
+    g = geom.c()
+    _check(lib().lcsa_block_importance_static(ctypes.byref(g), pooled_q.data_ptr(), cache.handle, scale, _stream(stream)),
+           "lcsa_block_importance_static")
     return lcsa_cache_importance(cache)
 
 

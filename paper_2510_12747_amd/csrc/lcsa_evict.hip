@@ -15,10 +15,21 @@
 // Everything is deterministic: no atomics, fixed summation orders.
 #include "lcsa_kernels.h"
 
+#include <mutex>
+
 namespace lcsa {
 namespace {
 
 constexpr int kThreads = 256;
+
+// Scratch of the entry point that allocates nothing: the per-row partial sums of the importance kernels,
+// held by every GPU the library runs on until the process ends.  The name below is only a host-side handle
+// of the symbol; host code uses the per-device address that hipGetSymbolAddress returns.
+__device__ __align__(256) float scratch[kStaticScratchFloats];
+
+constexpr int kMaxDevices = 64;
+float *g_scratch_ptr[kMaxDevices];      // address of `scratch` on each device, looked up once
+std::mutex g_scratch_mutex;
 
 __global__ __launch_bounds__(kThreads) void importance_rows_kernel(KGeom g, KCache c, const float *__restrict__ pooled_q,
                                                                    float scale, float *__restrict__ row_group) {
@@ -149,6 +160,27 @@ hipError_t launch_importance(const KGeom &g, const KCache &c, const float *poole
     if (e != hipSuccess) return e;
     importance_sum_kernel<<<dim3(g.heads), dim3((g.cap + 63) / 64 * 64), 0, stream>>>(row_group, imp, n_qb, g.cap);
     return hipGetLastError();
+}
+
+hipError_t launch_importance_static(const KGeom &g, const KCache &c, const float *pooled_q, float scale,
+                                    float *imp, int max_cand, hipStream_t stream) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    float *ptr;
+    {
+        std::lock_guard<std::mutex> lock(g_scratch_mutex);
+        if (!g_scratch_ptr[dev]) {          // first call on this device, which is the current one
+            void *p = nullptr;
+            e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+            if (e != hipSuccess) return e;
+            g_scratch_ptr[dev] = (float *)p;
+        }
+        ptr = g_scratch_ptr[dev];
+    }
+    // every row of the scratch that the second kernel reads is written in full by the first: nothing to clear
+    return launch_importance(g, c, pooled_q, scale, ptr, imp, max_cand, stream);
 }
 
 hipError_t launch_evict(const KGeom &g, int32_t *order, const float *imp, int valid, int n_new, int n_evict,

@@ -272,6 +272,21 @@ int32_t lcsa_block_importance(const lcsa_geom *geom, const float *pooled_q, lcsa
     return hip_status(e);
 }
 
+int32_t lcsa_block_importance_static(const lcsa_geom *geom, const float *pooled_q, lcsa_cache *cache, float scale, void *stream) {
+    if (!geom_ok(geom) || !cache || !pooled_q) return LCSA_EINVAL;
+    if (!same_geom(geom, cache->geom)) return LCSA_EINVAL;
+    KGeom kg = derive(*geom);
+    // the limit of the static array is a property of the geometry: checked before the state of the cache
+    if ((int64_t)kg.heads * kg.q_groups * kg.nb * kg.cap > kStaticScratchFloats) return LCSA_EUNSUPPORTED;
+    if (cache->kc.valid * geom->tile_t < geom->q_frames) return LCSA_EINVAL;
+    const int mc = max_candidates(kg, cache->kc.valid);
+    if (mc > 8192 || kg.cap > 1024) return LCSA_EUNSUPPORTED;
+    if (!(scale > 0.f)) scale = 1.0f / sqrtf((float)kg.d);
+    const hipError_t e = launch_importance_static(kg, cache->kc, pooled_q, scale, cache->importance, mc, (hipStream_t)stream);
+    if (e == hipSuccess) cache->scored = true;
+    return hip_status(e);
+}
+
 int32_t lcsa_sparse_attn_fwd(const lcsa_geom *geom, const void *q, int64_t q_stride_tok, int64_t q_stride_head,
                              const lcsa_cache *cache, const int32_t *sel_idx, const int32_t *sel_cnt,
                              void *o, int64_t o_stride_tok, int64_t o_stride_head,

@@ -96,6 +96,13 @@ hipError_t launch_append(const KGeom &g, const KCache &c, const void *k, const v
 hipError_t launch_importance(const KGeom &g, const KCache &c, const float *pooled_q, float scale,
                              float *row_group, float *imp, int max_cand, hipStream_t stream);
 
+// The same with the scratch in a static device array of kStaticScratchFloats floats that the library holds on
+// every GPU it runs on (no caller memory beyond inputs and outputs); needs heads*n_qb*cap <= that many floats.
+// Runs on the current device, to which `stream` must belong.
+constexpr int kStaticScratchFloats = 1 << 18;
+hipError_t launch_importance_static(const KGeom &g, const KCache &c, const float *pooled_q, float scale,
+                                    float *imp, int max_cand, hipStream_t stream);
+
 // Importance-based eviction before an append of n_new groups: drops the n_evict least important of the
 // `valid` visible groups of every head (uniform: by the sum over heads), gives the arrivals the free
 // slots, and rewrites order[heads][cap].  scored = false: imp is not read and every group counts as 0
