@@ -2,18 +2,23 @@
 """Benchmark of the locality-constrained block-sparse attention hot path on one MI355X.
 
 One STEP = one chunk of latent frames through every layer of the workload: per layer
-lcsa_kv_cache_append -> lcsa_pool_blocks -> lcsa_select_blocks -> lcsa_sparse_attn_fwd, each
-layer with its own seeded Q/K/V and its own sliding-window cache (already primed, so the timed
-step runs in steady state: append evicts the oldest frames, attention sees a full window).
-Inputs are resident in HBM before the timed region.  Prints ONE JSON line.
+lcsa_kv_cache_append -> lcsa_pool_select_blocks -> lcsa_sparse_attn_fwd, each layer with its own seeded
+Q/K/V and its own sliding-window cache (already primed, so the timed step runs in steady state: append
+evicts the oldest frames, attention sees a full window).  Inputs are resident in HBM before the timed
+region.  Prints ONE JSON line: the headline workload (default: paper-scale, the configuration the metric is
+quoted on), then, outside the timed region, short measurements of the other benchmark configurations
+("other_workloads"), what the chip sustains on trivial loops ("measured_peaks"), per-workgroup time stamps of
+the attention kernel ("attn_timers") and the CPU oracle on a bounded sample ("cpu_baseline").
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload paper|small|ultra|4k]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload paper|small|ultra|4k|tiny]
 """
 from __future__ import annotations
 
 import argparse
+import ctypes
 import json
 import os
+import re
 import sys
 import time
 from concurrent.futures import ThreadPoolExecutor
@@ -24,14 +29,11 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 / fp16 matrix peak
+PEAK_F32_TFLOPS = 157.3        # vector fp32 (the generic kernels of the Tiny configuration)
 PEAK_HBM_GBS = 8000.0
 
-# HBM-side bytes per attention launch (L2 <-> fabric), from the rocprofv3 --pmc passes summarised in
-# profiles/hot_path_paper_scale_pmc.txt: FETCH_SIZE x 2.0 (factor from a 1 GiB copy) + WRITE_SIZE x 1.0, in bytes.
-# Counters cannot be read from inside this script; the figure is only quoted for the workload it was taken on.
-ATTN_TRAFFIC_BYTES = {("paper", 32): 278.9e6 + 25.9e6}
-
 WORKLOAD_TEXT = {
+    "tiny": "tiny: 6x8 tokens/frame, 1 head, d=32, fp32, 2 query + 2 cached frames, 4x4 tiles, radius 4, top-k 4",
     "paper": "paper-scale 768x1408: 48x88 tokens/frame, 2 query + 4 cached frames, 8x16 tiles, radius 24, top-k 32, 30 layer calls",
     "small": "small-video 384x704: 24x44 tokens/frame, 2 query + 4 cached frames, 8x16 tiles, radius 16, top-k 16",
     "ultra": "ultra-high-res 1440x2560: 90x160 tokens/frame, 2 query + 4 cached frames, 8x16 tiles, radius 24, top-k 32",
@@ -39,43 +41,64 @@ WORKLOAD_TEXT = {
 }
 
 
-def main() -> int:
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=10)
-    ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="paper", choices=sorted(WORKLOAD_TEXT))
-    ap.add_argument("--layers", type=int, default=0, help="override the workload's number of layer calls")
-    ap.add_argument("--topk", type=int, default=0, help="override top-k (a value >= the window size gives windowed dense attention)")
-    ap.add_argument("--radius", type=int, default=None, help="override the locality radius in tokens (-1: unbounded window)")
-    ap.add_argument("--blocks", default="", help="block shape t,h,w overriding the workload's 1,tile_h,tile_w (e.g. 2,8,8: the paper's partition)")
-    ap.add_argument("--grid", default="", help="latent grid h,w overriding the workload's (e.g. 96,168: a 1536x2688 video)")
-    ap.add_argument("--cache-frames", type=int, default=0, help="override the sliding-window capacity in frames")
-    ap.add_argument("--eviction", default="sliding", choices=["sliding", "headwise", "uniform"],
-                    help="KV-cache eviction: the paper's default sliding window, or importance-based (adds lcsa_block_importance to every layer call)")
-    ap.add_argument("--graph", action="store_true",
-                    help="replay the layer calls of a step from captured HIP graphs (the caches are full when they are recorded)")
-    ap.add_argument("--two-calls", action="store_true",
-                    help="pool and select with lcsa_pool_blocks + lcsa_select_blocks instead of the fused lcsa_pool_select_blocks")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--calibrate-copy", action="store_true",
-                    help="also run one 1 GiB device-to-device copy (reference point for HBM byte counters)")
-    args = ap.parse_args()
-    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build measures ONE GPU (the path has no inter-GPU part); run with --gpus 1", file=sys.stderr)
-        return 2
+def attn_traffic_from_profiles(workload: str, topk: int):
+    """HBM-side bytes of one attention launch (L2 <-> fabric) as the rocprofv3 --pmc summaries under profiles/
+    state them: a line `TRAFFIC attn_mfma_kernel workload=<w> topk=<k> fetch_bytes=<f> write_bytes=<w>`
+    (FETCH_SIZE and WRITE_SIZE already scaled by the factors a plain copy of known size gives, as that file
+    says).  Counters cannot be read from inside this script; None if no summary covers the workload."""
+    pat = re.compile(rf"^TRAFFIC attn_mfma_kernel workload={workload} topk={topk} fetch_bytes=([0-9.e+]+) write_bytes=([0-9.e+]+)")
+    pdir = os.path.join(ROOT, "profiles")
+    if not os.path.isdir(pdir):
+        return None
+    for name in sorted(os.listdir(pdir)):
+        if not name.endswith(".txt"):
+            continue
+        for line in open(os.path.join(pdir, name)):
+            m = pat.match(line)
+            if m:
+                return float(m.group(1)) + float(m.group(2))
+    return None
 
-    import torch
-    from paper_2510_12747_amd import binding as B
-    from paper_2510_12747_amd import workloads as wl
 
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible", file=sys.stderr)
-        return 2
-    B.lib()   # fail loudly if the HIP library is not built
+class Aids:
+    """libbench_probe.so: measurement aids that are not part of the library (built by __graft_entry__.build())."""
 
-    w = wl.WORKLOADS[args.workload]
-    n_layers = args.layers or w.n_layers
+    def __init__(self):
+        path = os.path.join(ROOT, "libbench_probe.so")
+        self.lib = ctypes.CDLL(path) if os.path.exists(path) else None
+        if self.lib:
+            vp, i32, i64, f32 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_float
+            self.lib.bench_probe_mfma_bf16.argtypes = [vp, i32, i32, vp]
+            self.lib.bench_mock_loop.argtypes = [i32, vp, vp, i32, i32, vp]
+            self.lib.bench_attn_timed.argtypes = [vp, vp, i64, i64, vp, vp, vp, vp, i64, i64, f32, vp, vp]
+            for f in (self.lib.bench_probe_mfma_bf16, self.lib.bench_mock_loop, self.lib.bench_attn_timed):
+                f.restype = i32
+
+
+def valid_tokens_per_block(w, tile_t):
+    ty, tx = -(-w.grid_h // w.tile_h), -(-w.grid_w // w.tile_w)
+    vh = np.minimum(w.tile_h, w.grid_h - np.arange(ty) * w.tile_h)
+    vw = np.minimum(w.tile_w, w.grid_w - np.arange(tx) * w.tile_w)
+    return (vh[:, None] * vw[None, :]).reshape(-1) * tile_t
+
+
+def attention_flop(sel_idx, valid_tok, n_qb, nb, d):
+    """(useful, issued) flop of one attention launch from the selection actually made: 4 d sum valid_q valid_k;
+    issued = the same with valid counts rounded up to the 32 x 32 tiles the matrix-core kernel computes."""
+    idx = sel_idx.cpu().numpy()
+    up32 = -(-valid_tok // 32) * 32
+    q_tiles = np.arange(n_qb) % nb
+    kvalid = np.where(idx >= 0, valid_tok[np.maximum(idx, 0) % nb], 0).sum(axis=-1)   # [h][qb]
+    kiss = np.where(idx >= 0, up32[np.maximum(idx, 0) % nb], 0).sum(axis=-1)
+    return (4.0 * d * float((valid_tok[q_tiles][None, :] * kvalid).sum()),
+            4.0 * d * float((up32[q_tiles][None, :] * kiss).sum()))
+
+
+def measure(torch, B, wl, args, name, steps, warmup, n_layers=None):
+    """Sets up the layer calls of a workload (caches primed), times `steps` steps and returns the figures plus
+    the live objects (for the aids that run afterwards)."""
+    w = wl.WORKLOADS[name]
+    n_layers = n_layers or args.layers or w.n_layers
     topk = args.topk or w.topk
     radius = w.radius if args.radius is None else args.radius
     tile_t = 1
@@ -87,15 +110,18 @@ def main() -> int:
         w = wl.with_overrides(w, grid_h=gh, grid_w=gw)
     if args.cache_frames:
         w = wl.with_overrides(w, cache_frames=args.cache_frames)
+    bf16 = w.dtype == "bf16"
     g = B.Geom(w.heads, w.head_dim, w.grid_h, w.grid_w, w.tile_h, w.tile_w, w.q_frames, w.cache_frames,
-               radius, radius, topk, dtype=B.LCSA_BF16, tile_t=tile_t)
+               radius, radius, topk, dtype=B.LCSA_BF16 if bf16 else B.LCSA_F32, tile_t=tile_t)
     n_qb = g.n_qb
     policy = {"sliding": B.LCSA_EVICT_SLIDING, "headwise": B.LCSA_EVICT_IMPORTANCE_HEADWISE,
               "uniform": B.LCSA_EVICT_IMPORTANCE_UNIFORM}[args.eviction]
     scoring = policy != B.LCSA_EVICT_SLIDING
 
     def dev(x):
-        return torch.from_numpy(wl.bf16_bits(x).view(np.int16)).view(torch.bfloat16).cuda()
+        if bf16:
+            return torch.from_numpy(wl.bf16_bits(x).view(np.int16)).view(torch.bfloat16).cuda()
+        return torch.from_numpy(np.ascontiguousarray(x, np.float32)).cuda()
 
     # ---- setup: seeded inputs per layer (host, threads), caches primed ---------------------------
     t0 = time.time()
@@ -148,22 +174,15 @@ def main() -> int:
             B.lcsa_block_importance(g, L["pq"], L["cache"])     # scores the visible groups for the next append
         if ev: ev[5].record()
 
-    if args.calibrate_copy:
-        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
-        dst = torch.empty_like(src)
-        dst.copy_(src)
-        torch.cuda.synchronize()
-        del src, dst
-
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         for L in layers:
             layer_call(L)
     torch.cuda.synchronize()
 
-    # ---- timed region: exactly K steps; HIP events around every attention launch ------------------
+    # ---- timed region: exactly `steps` steps; HIP events around every attention launch ------------
     # (all launches go to torch's current stream, which is the stream these events are recorded on)
     attn_ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in layers]
-               for _ in range(args.steps)]
+               for _ in range(steps)]
     graphs = []
     if args.graph:
         # one graph per position of the chunk rotation: the inputs of a captured call are fixed
@@ -173,23 +192,23 @@ def main() -> int:
                 for L in layers:
                     layer_call(L)
             graphs.append(gph)
-        for s_ in range(args.warmup):
+        for s_ in range(warmup):
             graphs[s_ % len(graphs)].replay()
     torch.cuda.synchronize()
     t_start = time.perf_counter()
-    for s in range(args.steps):
+    for s in range(steps):
         if args.graph:
-            graphs[(args.warmup + s) % len(graphs)].replay()
+            graphs[(warmup + s) % len(graphs)].replay()
         else:
             for L, (e0, e1) in zip(layers, attn_ev[s]):
                 layer_call(L, attn_ev=(e0, e1))
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t_start
-    ms_per_step = elapsed * 1e3 / args.steps
+    ms_per_step = elapsed * 1e3 / steps
     ms_per_layer = ms_per_step / n_layers
     attn_ms = None if args.graph else np.array([[e0.elapsed_time(e1) for (e0, e1) in step] for step in attn_ev])
 
-    # ---- untimed breakdown pass: events between the four calls ------------------------------------
+    # ---- untimed breakdown pass: events between the calls ------------------------------------------
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in layers]
     for L, e in zip(layers, ev):
         e[4].record()
@@ -200,82 +219,28 @@ def main() -> int:
     if attn_ms is None:      # launches inside a graph carry no events: the attention launches of this eager pass stand in
         attn_ms = np.array([[e[2].elapsed_time(e[3]) for e in ev]])
 
-    # ---- what this chip sustains on trivial loops, quoted beside the nominal peaks (outside the timed region):
-    # back-to-back bf16 matrix instructions on registers, and a 1 GiB device-to-device copy
-    prop = torch.cuda.get_device_properties(0)
-    n_cu = prop.multi_processor_count
-    pe = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
-    probe_tflops = None
-    probe_path = os.path.join(ROOT, "libbench_probe.so")      # bench-only shared object, built by __graft_entry__.build()
-    if os.path.exists(probe_path):
-        import ctypes
-        probe = ctypes.CDLL(probe_path).bench_probe_mfma_bf16
-        probe.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p]
-        probe.restype = ctypes.c_int32
-        probe_out = torch.empty(n_cu * 2 * 512, dtype=torch.float32, device="cuda")
-        probe_iters = 4000
-        cur = torch.cuda.current_stream().cuda_stream
-        assert probe(probe_out.data_ptr(), n_cu * 2, 200, cur) == 0
-        pe[0].record()
-        assert probe(probe_out.data_ptr(), n_cu * 2, probe_iters, cur) == 0
-        pe[1].record()
-        torch.cuda.synchronize()
-        probe_tflops = n_cu * 2 * 8 * probe_iters * 32 * 32768.0 / (pe[0].elapsed_time(pe[1]) * 1e-3) / 1e12
-        del probe_out
-    csrc = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
-    cdst = torch.empty_like(csrc)
-    cdst.copy_(csrc)
-    pe[0].record()
-    for _ in range(5):
-        cdst.copy_(csrc)
-    pe[1].record()
-    torch.cuda.synchronize()
-    copy_gbs = 5 * 2 * float(1 << 30) / (pe[0].elapsed_time(pe[1]) * 1e-3) / 1e9
-    del csrc, cdst
-
     # ---- algorithmic work of one attention launch (from the selection actually made) ---------------
-    ty, tx = -(-w.grid_h // w.tile_h), -(-w.grid_w // w.tile_w)
-    vh = np.minimum(w.tile_h, w.grid_h - np.arange(ty) * w.tile_h)
-    vw = np.minimum(w.tile_w, w.grid_w - np.arange(tx) * w.tile_w)
-    valid_tok = (vh[:, None] * vw[None, :]).reshape(-1) * tile_t     # valid tokens per block
-    useful, issued = [], []
-    for L in layers:
-        idx = L["sel_idx"].cpu().numpy()
-        cnt = L["sel_cnt"].cpu().numpy()
-        kvalid = np.where(idx >= 0, valid_tok[np.maximum(idx, 0) % g.nb], 0).sum(axis=-1)   # [h][qb]
-        qvalid = valid_tok[np.arange(n_qb) % g.nb][None, :]
-        useful.append(4.0 * g.head_dim * float((qvalid * kvalid).sum()))
-        # the kernel computes whole 32-query x 32-key matrix-core tiles: valid counts rounded up to 32
-        up32 = -(-valid_tok // 32) * 32
-        kiss = np.where(idx >= 0, up32[np.maximum(idx, 0) % g.nb], 0).sum(axis=-1)
-        qiss = up32[np.arange(n_qb) % g.nb][None, :]
-        issued.append(4.0 * g.head_dim * float((qiss * kiss).sum()))
-    useful_flop, issued_flop = float(np.mean(useful)), float(np.mean(issued))
+    valid_tok = valid_tokens_per_block(w, tile_t)
+    flops = [attention_flop(L["sel_idx"], valid_tok, n_qb, g.nb, g.head_dim) for L in layers]
+    useful_flop, issued_flop = float(np.mean([f[0] for f in flops])), float(np.mean([f[1] for f in flops]))
     attn_avg_ms = float(attn_ms.mean())
     achieved = useful_flop / (attn_avg_ms * 1e-3) / 1e12
 
-    # append traffic (algorithmic): read new K,V once, write their tiles once, write pooled K
+    elt = 2 if bf16 else 4
+    bt = tile_t * w.tile_h * w.tile_w
     tok_new = w.q_frames * w.tokens_per_frame
-    append_bytes = 2 * tok_new * g.heads * g.head_dim * 2 + 2 * n_qb * 128 * 128 * 2 * g.heads \
+    # append traffic (algorithmic): read new K,V once, write their tiles once, write pooled K
+    append_bytes = 2 * tok_new * g.heads * g.head_dim * elt + 2 * n_qb * bt * g.head_dim * elt * g.heads \
         + n_qb * g.heads * g.head_dim * 4
-    pool_bytes = tok_new * g.heads * g.head_dim * 2 + n_qb * g.heads * g.head_dim * 4
+    pool_bytes = tok_new * g.heads * g.head_dim * elt + n_qb * g.heads * g.head_dim * 4
     # selection: pooled Q and the pooled K of every visible block once, ids + counts out
     select_bytes = (n_qb + w.cache_frames // tile_t * g.nb) * g.heads * g.head_dim * 4 + g.heads * n_qb * (topk + 1) * 4
-
-    out = {
-        "metric": "sparse_attn_ms_per_chunk_per_layer",
-        "value": round(ms_per_layer, 5),
-        "unit": "ms",
-        "n_gpus": 1,
-        "steps": args.steps,
-        "warmup": args.warmup,
-        "ms_per_step": round(ms_per_step, 4),
-        "higher_is_better": False,
-        "scaling": "weak",
-        "vs_baseline": None,
-        "dtype": "bf16",
-        "data": "synthetic",
-        "config": {"workload": WORKLOAD_TEXT[args.workload], "heads": g.heads, "head_dim": g.head_dim,
+    mfma_path = bf16 and g.head_dim == 128 and bt == 128
+    peak = PEAK_BF16_TFLOPS if mfma_path else PEAK_F32_TFLOPS
+    plain = not (args.blocks or args.grid or args.cache_frames) and args.radius is None and policy == B.LCSA_EVICT_SLIDING
+    res = {
+        "ms_per_layer": ms_per_layer, "ms_per_step": ms_per_step,
+        "config": {"workload": WORKLOAD_TEXT[name], "heads": g.heads, "head_dim": g.head_dim,
                    "layers_per_step": n_layers, "q_tokens": tok_new, "kv_tokens": w.cache_frames * w.tokens_per_frame,
                    "block_shape": [tile_t, w.tile_h, w.tile_w], "blocks_per_group": g.nb, "query_blocks": n_qb,
                    "grid": [w.grid_h, w.grid_w], "cache_frames": w.cache_frames, "topk": topk, "radius": radius,
@@ -290,54 +255,238 @@ def main() -> int:
                     **({"pool_blocks": round(pool_bytes / (brk[1] * 1e-3) / 1e9, 1),
                         "select_blocks": round(select_bytes / (brk[2] * 1e-3) / 1e9, 1)} if args.two_calls else
                        {"pool_select_blocks": round((pool_bytes + select_bytes) / (brk[2] * 1e-3) / 1e9, 1)})},
-        "device": {"name": prop.name, "compute_units": n_cu,
-                   "nominal_peak_tflops": PEAK_BF16_TFLOPS, "nominal_hbm_gbs": 8000.0},
-        "measured_peaks": {"mfma_bf16_register_loop_tflops": round(probe_tflops, 1) if probe_tflops else None,
-                           "device_copy_gbs": round(copy_gbs, 1)},
-        "roofline": {"kernel": "attn_mfma_kernel", "bound": "mfma", "achieved": round(achieved, 2),
-                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
-                     "traffic": ATTN_TRAFFIC_BYTES.get((args.workload, topk)) if not (args.blocks or args.grid or args.cache_frames) and args.radius is None and policy == B.LCSA_EVICT_SLIDING else None,
+        "roofline": {"kernel": "attn_mfma_kernel" if mfma_path else "attn_generic_kernel",
+                     "bound": "mfma" if mfma_path else "alu", "achieved": round(achieved, 3),
+                     "peak": peak, "unit": "TFLOP/s", "frac": round(achieved / peak, 4),
+                     "traffic": attn_traffic_from_profiles(name, topk) if plain and mfma_path else None,
                      "flop_per_launch_useful": useful_flop, "flop_per_launch_issued": issued_flop,
-                     "issued_tflops": round(issued_flop / (attn_avg_ms * 1e-3) / 1e12, 2),
-                     "avg_launch_ms": round(attn_avg_ms, 5), "min_launch_ms": round(float(attn_ms.min()), 5),
-                     # beside the nominal peak: the same figure against what a register-only MFMA loop sustains here
-                     "frac_of_measured_mfma_loop": round(achieved / probe_tflops, 4) if probe_tflops else None},
+                     "issued_tflops": round(issued_flop / (attn_avg_ms * 1e-3) / 1e12, 3),
+                     "avg_launch_ms": round(attn_avg_ms, 5), "min_launch_ms": round(float(attn_ms.min()), 5)},
         "setup_s": round(setup_s, 1),
     }
+    live = dict(w=w, g=g, layers=layers, host_layer0=host_layer0, gen=gen, tile_t=tile_t, radius=radius, topk=topk,
+                n_layers=n_layers, dev=dev, mfma_path=mfma_path)
+    return res, live
 
-    # ---- streaming workloads: one video from an empty cache, chunk by chunk, for three top-k values -----
-    # (per-chunk time of the whole path while the ring fills and in the steady state; outside the timed region)
+
+def streaming_sweep(torch, B, wl, live, topks=(16, 32, 64)):
+    """One video from an empty cache, chunk by chunk, for several top-k values: per-chunk time of the whole path
+    while the ring fills and in the steady state (attention launches timed separately)."""
+    w, g0, dev, tile_t, radius = live["w"], live["g"], live["dev"], live["tile_t"], live["radius"]
+    s0 = wl.ChunkStream(w, 0)
+    vchunks = [tuple(dev(x) for x in s0.next()) for _ in range(w.n_chunks)]
+    fill = (w.cache_frames - w.q_frames) // w.q_frames           # chunks before the ring is full
+    n_qb = g0.n_qb
+    valid_tok = valid_tokens_per_block(w, tile_t)
+    out = {}
+    for rep, k in enumerate((topks[0],) + tuple(topks)):              # the first pass only warms up
+        gk = B.Geom(w.heads, w.head_dim, w.grid_h, w.grid_w, w.tile_h, w.tile_w, w.q_frames, w.cache_frames,
+                    radius, radius, k, dtype=g0.dtype, tile_t=tile_t)
+        cache = B.lcsa_cache_init(gk)
+        pq = torch.empty(gk.heads, n_qb, gk.head_dim, dtype=torch.float32, device="cuda")
+        si = torch.empty(gk.heads, n_qb, k, dtype=torch.int32, device="cuda")
+        sc = torch.empty(gk.heads, n_qb, dtype=torch.int32, device="cuda")
+        oo = torch.empty_like(vchunks[0][0])
+        evs = [torch.cuda.Event(enable_timing=True) for _ in range(len(vchunks) + 1)]
+        aev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in vchunks]
+        torch.cuda.synchronize()
+        evs[0].record()
+        for i, (qd, kd, vd) in enumerate(vchunks):
+            B.lcsa_kv_cache_append(cache, kd, vd, w.q_frames)
+            B.lcsa_pool_select_blocks(gk, qd, cache, pq, si, sc, want_gap=False)
+            aev[i][0].record()
+            B.lcsa_sparse_attn_fwd(gk, qd, cache, si, sc, oo)
+            aev[i][1].record()
+            evs[i + 1].record()
+        torch.cuda.synchronize()
+        ms = [evs[i].elapsed_time(evs[i + 1]) for i in range(len(vchunks))]
+        ams = [a.elapsed_time(b) for a, b in aev]
+        if rep:
+            flop, _ = attention_flop(si, valid_tok, n_qb, gk.nb, gk.head_dim)      # a steady-state launch: the last selection
+            steady_attn = float(np.mean(ams[fill:]))
+            out[f"topk_{k}"] = {"ring_filling_ms_per_chunk": [round(x, 4) for x in ms[:fill]],
+                                "steady_ms_per_chunk_mean": round(float(np.mean(ms[fill:])), 4),
+                                "steady_ms_per_chunk_min": round(float(np.min(ms[fill:])), 4),
+                                "steady_attn_ms": round(steady_attn, 4),
+                                "steady_attn_tflops": round(flop / (steady_attn * 1e-3) / 1e12, 1),
+                                "steady_attn_roofline_frac": round(flop / (steady_attn * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4)}
+        del cache, pq, si, sc, oo
+    return {"chunks": len(vchunks), "chunks_before_ring_is_full": fill, **out}
+
+
+def attn_timers(torch, B, aids, live):
+    """Time stamps of every workgroup of one attention launch (layer 0 of the workload as it stands): shader clock
+    under load and time per workgroup, for the workgroups that start with the launch (one per compute unit) and
+    for those that start later (on fewer busy compute units).  Stamps inside the kernel (before and after the
+    main loop, -DLCSA_TIMERS=1) slow its loop by 16 %, so the aid is built with entry and exit stamps only."""
+    g, L = live["g"], live["layers"][0]
+    q = L["chunks"][(L["turn"] - 1) % len(L["chunks"])][0]
+    total = g.heads * g.n_qb
+    n_wg = 8 * -(-((total + 1) // 2) // 8)
+    stamps = torch.zeros(n_wg, 10, dtype=torch.int64, device="cuda")
+    gc = g.c()
+    cnt = L["sel_cnt"].cpu().numpy()
+    for _ in range(3):                                   # the last of three launches is read (the first ones warm up)
+        stamps.zero_()
+        rc = aids.lib.bench_attn_timed(ctypes.byref(gc), q.data_ptr(), q.stride(0), q.stride(1), L["cache"].handle,
+                                       L["sel_idx"].data_ptr(), L["sel_cnt"].data_ptr(), L["o"].data_ptr(),
+                                       L["o"].stride(0), L["o"].stride(1), 0.0, stamps.data_ptr(),
+                                       torch.cuda.current_stream().cuda_stream)
+        if rc != 0:
+            return None
+        torch.cuda.synchronize()
+    t = stamps.cpu().numpy().astype(np.float64)
+    t = t[t[:, 0] > 0]
+    if len(t) == 0:
+        return None
+    clk = lambda a, b: (t[:, 2 * b] - t[:, 2 * a])                    # shader cycles between stamps a and b
+    wall = lambda a, b: (t[:, 2 * b + 1] - t[:, 2 * a + 1]) * 10.0     # ns (100 MHz counter)
+    steps = int(cnt.max()) + 1                                         # loop iterations of a full workgroup
+    start_ns = (t[:, 1] - t[:, 1].min()) * 10.0
+    first = start_ns < 0.25 * wall(0, 3).mean()                        # workgroups that started with the launch
+
+    def rnd(sel):
+        if sel.sum() == 0:
+            return None
+        return {"workgroups": int(sel.sum()),
+                "shader_clock_ghz": round(float(clk(0, 3)[sel].sum() / wall(0, 3)[sel].sum()), 3),
+                "us_per_workgroup": round(float(np.median(wall(0, 3)[sel])) / 1e3, 2),
+                "shader_cycles_per_workgroup": round(float(np.median(clk(0, 3)[sel]))),
+                "shader_cycles_per_loop_step_incl_setup_and_epilogue": round(float(np.median(clk(0, 3)[sel])) / steps, 1)}
+
+    span = (t[:, 7].max() - t[:, 1].min()) * 10.0
+    return {"kernel": "attn_mfma_kernel built with -DLCSA_TIMERS=2 (libbench_probe.so): stamps at entry and exit of every workgroup",
+            "workgroups_that_ran": int(len(t)), "loop_steps_per_workgroup": steps,
+            "matrix_cycles_per_loop_step_per_simd": 4096,
+            "first_stamp_to_last_stamp_us": round(float(span) / 1e3, 2),
+            "started_with_the_launch": rnd(first), "started_later": rnd(~first)}
+
+
+def trivial_loops(torch, aids):
+    """What this chip sustains on trivial loops, quoted beside the nominal peaks."""
+    prop = torch.cuda.get_device_properties(0)
+    n_cu = prop.multi_processor_count
+    pe = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    cur = torch.cuda.current_stream().cuda_stream
+    out = {"mfma_bf16_register_loop_tflops": None, "mock_inner_loop_tflops": None}
+    if aids.lib:
+        buf = torch.empty(n_cu * 2 * 512, dtype=torch.float32, device="cuda")
+        iters = 4000
+        assert aids.lib.bench_probe_mfma_bf16(buf.data_ptr(), n_cu * 2, 200, cur) == 0
+        pe[0].record()
+        assert aids.lib.bench_probe_mfma_bf16(buf.data_ptr(), n_cu * 2, iters, cur) == 0
+        pe[1].record()
+        torch.cuda.synchronize()
+        out["mfma_bf16_register_loop_tflops"] = round(n_cu * 2 * 8 * iters * 32 * 32768.0 / (pe[0].elapsed_time(pe[1]) * 1e-3) / 1e12, 1)
+        src = torch.ones(16 << 20, dtype=torch.uint8, device="cuda")
+        mock = {}
+        for variant, label in ((0, "mfma+lds_operands"), (1, "+4_valu_per_mfma"), (2, "+barrier_per_32_mfma"),
+                               (3, "+tile_copies (the full mix)"), (4, "the full mix with 5 valu"),
+                               (5, "the full mix without mfma: ns per step")):
+            steps = 3000
+            assert aids.lib.bench_mock_loop(variant, buf.data_ptr(), src.data_ptr(), n_cu, 50, cur) == 0
+            pe[0].record()
+            assert aids.lib.bench_mock_loop(variant, buf.data_ptr(), src.data_ptr(), n_cu, steps, cur) == 0
+            pe[1].record()
+            torch.cuda.synchronize()
+            ms = pe[0].elapsed_time(pe[1])
+            mock[label] = round(ms * 1e6 / steps, 1) if variant == 5 else round(n_cu * 8 * 32 * 32768.0 * steps / (ms * 1e-3) / 1e12, 1)
+        out["mock_inner_loop_tflops"] = mock
+        del buf, src
+    csrc = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
+    cdst = torch.empty_like(csrc)
+    cdst.copy_(csrc)
+    pe[0].record()
+    for _ in range(5):
+        cdst.copy_(csrc)
+    pe[1].record()
+    torch.cuda.synchronize()
+    out["device_copy_gbs"] = round(5 * 2 * float(1 << 30) / (pe[0].elapsed_time(pe[1]) * 1e-3) / 1e9, 1)
+    del csrc, cdst
+    return out, prop, n_cu
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="paper", choices=sorted(WORKLOAD_TEXT))
+    ap.add_argument("--layers", type=int, default=0, help="override the workload's number of layer calls")
+    ap.add_argument("--topk", type=int, default=0, help="override top-k (a value >= the window size gives windowed dense attention)")
+    ap.add_argument("--radius", type=int, default=None, help="override the locality radius in tokens (-1: unbounded window)")
+    ap.add_argument("--blocks", default="", help="block shape t,h,w overriding the workload's 1,tile_h,tile_w (e.g. 2,8,8: the paper's partition)")
+    ap.add_argument("--grid", default="", help="latent grid h,w overriding the workload's (e.g. 96,168: a 1536x2688 video)")
+    ap.add_argument("--cache-frames", type=int, default=0, help="override the sliding-window capacity in frames")
+    ap.add_argument("--eviction", default="sliding", choices=["sliding", "headwise", "uniform"],
+                    help="KV-cache eviction: the paper's default sliding window, or importance-based (adds lcsa_block_importance to every layer call)")
+    ap.add_argument("--graph", action="store_true",
+                    help="replay the layer calls of a step from captured HIP graphs (the caches are full when they are recorded)")
+    ap.add_argument("--two-calls", action="store_true",
+                    help="pool and select with lcsa_pool_blocks + lcsa_select_blocks instead of the fused lcsa_pool_select_blocks")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-others", action="store_true", help="skip the short measurements of the other benchmark configurations")
+    ap.add_argument("--no-aids", action="store_true", help="skip the trivial-loop rates and the kernel time stamps")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one 1 GiB device-to-device copy first (reference point for HBM byte counters)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build measures ONE GPU (the path has no inter-GPU part); run with --gpus 1", file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2510_12747_amd import binding as B
+    from paper_2510_12747_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    B.lib()   # fail loudly if the HIP library is not built
+    aids = Aids()
+
+    if args.calibrate_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
+    res, live = measure(torch, B, wl, args, args.workload, args.steps, args.warmup)
+    w = live["w"]
+    out = {
+        "metric": "sparse_attn_ms_per_chunk_per_layer",
+        "value": round(res["ms_per_layer"], 5),
+        "unit": "ms",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(res["ms_per_step"], 4),
+        "higher_is_better": False,
+        "scaling": "weak",
+        "vs_baseline": None,
+        # element type of Q, K, V, O and of the first matrix product; the second product takes probabilities and V
+        # as IEEE half (same matrix rate); every accumulation and the softmax are float
+        "dtype": "bf16" if w.dtype == "bf16" else "f32",
+        "data": "synthetic",
+        "config": res["config"],
+        "effective_tflops_whole_path": res["effective_tflops_whole_path"],
+        "kernel_ms_per_layer": res["kernel_ms_per_layer"],
+        "hbm_gbs": res["hbm_gbs"],
+        "roofline": res["roofline"],
+        "setup_s": res["setup_s"],
+    }
     if w.n_chunks > 1:
-        s0 = wl.ChunkStream(w, 0)
-        vchunks = [tuple(dev(x) for x in s0.next()) for _ in range(w.n_chunks)]
-        fill = (w.cache_frames - w.q_frames) // w.q_frames           # chunks before the ring is full
-        streaming = {}
-        for rep, k in enumerate((topk, 16, 32, 64)):                  # the first pass only warms up
-            gk = B.Geom(w.heads, w.head_dim, w.grid_h, w.grid_w, w.tile_h, w.tile_w, w.q_frames, w.cache_frames,
-                        radius, radius, k, dtype=B.LCSA_BF16, tile_t=tile_t)
-            cache = B.lcsa_cache_init(gk)
-            pq = torch.empty(gk.heads, n_qb, gk.head_dim, dtype=torch.float32, device="cuda")
-            si = torch.empty(gk.heads, n_qb, k, dtype=torch.int32, device="cuda")
-            sc = torch.empty(gk.heads, n_qb, dtype=torch.int32, device="cuda")
-            oo = torch.empty_like(vchunks[0][0])
-            evs = [torch.cuda.Event(enable_timing=True) for _ in range(len(vchunks) + 1)]
-            torch.cuda.synchronize()
-            evs[0].record()
-            for i, (qd, kd, vd) in enumerate(vchunks):
-                B.lcsa_kv_cache_append(cache, kd, vd, w.q_frames)
-                B.lcsa_pool_blocks(gk, qd, w.q_frames, pq)
-                B.lcsa_select_blocks(gk, pq, cache, si, sc, want_gap=False)
-                B.lcsa_sparse_attn_fwd(gk, qd, cache, si, sc, oo)
-                evs[i + 1].record()
-            torch.cuda.synchronize()
-            ms = [evs[i].elapsed_time(evs[i + 1]) for i in range(len(vchunks))]
-            if rep:
-                streaming[f"topk_{k}"] = {"ring_filling_ms_per_chunk": [round(x, 4) for x in ms[:fill]],
-                                          "steady_ms_per_chunk_mean": round(float(np.mean(ms[fill:])), 4),
-                                          "steady_ms_per_chunk_min": round(float(np.min(ms[fill:])), 4)}
-            del cache, pq, si, sc, oo
-        out["streaming"] = {"chunks": len(vchunks), "chunks_before_ring_is_full": fill, **streaming}
-        del vchunks
+        out["streaming"] = streaming_sweep(torch, B, wl, live)
+
+    if not args.no_aids:
+        if aids.lib and live["mfma_path"]:      # first: right after the timed region, in the same thermal state
+            out["attn_timers"] = attn_timers(torch, B, aids, live)
+        peaks, prop, n_cu = trivial_loops(torch, aids)
+        out["device"] = {"name": prop.name, "compute_units": n_cu, "nominal_peak_tflops": PEAK_BF16_TFLOPS,
+                         "nominal_hbm_gbs": PEAK_HBM_GBS}
+        out["measured_peaks"] = peaks
+        if peaks["mfma_bf16_register_loop_tflops"]:
+            out["roofline"]["frac_of_measured_mfma_loop"] = round(out["roofline"]["achieved"] / peaks["mfma_bf16_register_loop_tflops"], 4)
 
     # ---- CPU oracle on the host cores: a bounded sample of the same workload ------------------------
     # Whole layer calls (pooling, scores, selection, attention of every row) of the first layers of
@@ -345,10 +494,10 @@ def main() -> int:
     if not args.no_cpu_baseline:
         import oracle
         og = oracle.Geometry(w.heads, w.head_dim, w.grid_h, w.grid_w, w.tile_h, w.tile_w, w.q_frames,
-                             radius, radius, topk, tile_t=tile_t)
+                             live["radius"], live["radius"], live["topk"], tile_t=live["tile_t"])
         times = []
-        for layer in range(min(5, n_layers)):
-            chunks = host_layer0 if layer == 0 else gen(layer)
+        for layer in range(min(5, live["n_layers"])):
+            chunks = live["host_layer0"] if layer == 0 else live["gen"](layer)
             model = oracle.SlidingWindowCache(w.cache_frames)
             for (q, k, v) in chunks:
                 model.append(k, v, w.q_frames)
@@ -360,9 +509,29 @@ def main() -> int:
                 break
         out["cpu_baseline"] = {"value": round(float(np.mean(times)) * 1e3, 1), "unit": "ms", "cores": oracle.threads(),
                                "kind": "oracle",
-                               "sample": f"{len(times)} of {n_layers} layer calls of the same workload, each in full "
+                               "sample": f"{len(times)} of {live['n_layers']} layer calls of the same workload, each in full "
                                          f"(pool, scores, select, attend all rows); {sum(times):.1f} s of CPU time; "
                                          f"value = mean ms per chunk per layer"}
+    del live, res
+
+    # ---- the other benchmark configurations, briefly (outside the timed region of the headline) -------------
+    if not args.no_others and not (args.blocks or args.grid or args.cache_frames or args.topk or args.layers
+                                   or args.radius is not None):
+        others = {}
+        for name in ("tiny", "small", "paper", "ultra", "4k"):
+            if name == args.workload:
+                continue
+            torch.cuda.empty_cache()
+            r, lv = measure(torch, B, wl, args, name, steps=5, warmup=2, n_layers=2)
+            entry = {"ms_per_chunk_per_layer": round(r["ms_per_layer"], 5), "kernel_ms_per_layer": r["kernel_ms_per_layer"],
+                     "hbm_gbs": r["hbm_gbs"],
+                     "roofline": {k: r["roofline"][k] for k in ("kernel", "bound", "achieved", "peak", "unit", "frac", "traffic", "avg_launch_ms")},
+                     "layers_per_step": 2, "steps": 5}
+            if lv["w"].n_chunks > 1:
+                entry["streaming"] = streaming_sweep(torch, B, wl, lv)
+            others[name] = entry
+            del lv, r
+        out["other_workloads"] = others
     print(json.dumps(out))
     return 0
 

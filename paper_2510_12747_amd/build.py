@@ -32,11 +32,14 @@ def build(verbose: bool = False) -> str:
 
 
 def build_bench_aids(verbose: bool = False) -> str:
-    """bench.py's measurement aids (a register-only matrix-instruction loop), a shared object of their own."""
+    """bench.py's measurement aids (matrix-instruction loops, the attention kernel with time stamps), a shared
+    object of their own."""
     root = os.path.dirname(HERE)
     out = os.path.join(root, "libbench_probe.so")
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, *FLAGS, "-o", out, os.path.join(root, "bench_probe.hip")]
+    # the attention kernel once more, with its time stamps compiled in (the library's own copy has none)
+    cmd = [hipcc, *FLAGS, "-DLCSA_TIMERS=2", "-I", root, "-o", out, os.path.join(root, "bench_probe.hip"),
+           os.path.join(CSRC, "lcsa_attn_mfma.hip")]
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, capture_output=True, text=True)

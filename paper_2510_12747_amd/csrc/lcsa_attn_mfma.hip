@@ -37,6 +37,33 @@
 #include "lcsa_kernels.h"
 
 namespace lcsa {
+
+// Built with -DLCSA_TIMERS=1 (only the benchmark's measurement aids do that) the kernel also records, per
+// workgroup, the shader-clock counter and the constant 100 MHz counter at entry, before and after the main
+// loop and at exit (-DLCSA_TIMERS=2: at entry and exit only; the inner stamps perturb the loop's schedule
+// measurably), plus the hardware id of the compute unit: 10 x uint64 per workgroup at *d_attn_timers
+// (a device-side pointer variable rather than a kernel argument, which would cost scalar registers for the
+// whole kernel; null = no stamps).
+#ifdef LCSA_TIMERS
+__device__ uint64_t *d_attn_timers;
+hipError_t set_attn_timers(uint64_t *device_buffer) {
+    return hipMemcpyToSymbol(HIP_SYMBOL(d_attn_timers), &device_buffer, sizeof(device_buffer));
+}
+#define LCSA_STAMP(slot)                                                                                     \
+    if ((LCSA_TIMERS == 1 || (slot) == 0 || (slot) == 3) && threadIdx.x == 0) {                                                                                  \
+        uint64_t *timers = d_attn_timers;                                                                    \
+        if (timers) {                                                                                        \
+            timers[(size_t)blockIdx.x * 10 + 2 * (slot)] = __builtin_readcyclecounter();                     \
+            timers[(size_t)blockIdx.x * 10 + 2 * (slot) + 1] = __builtin_amdgcn_s_memrealtime();             \
+            if ((slot) == 0)      /* HW_ID (compute unit, shader engine) and, above it, XCC_ID (which of the 8 dies) */ \
+                timers[(size_t)blockIdx.x * 10 + 8] = (uint64_t)__builtin_amdgcn_s_getreg(4 | (31 << 11)) |  \
+                                                      (uint64_t)__builtin_amdgcn_s_getreg(20 | (31 << 11)) << 32; \
+        }                                                                                                    \
+    }
+#else
+#define LCSA_STAMP(slot)
+#endif
+
 namespace {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
@@ -124,6 +151,7 @@ __global__ __launch_bounds__(512, 2) void attn_mfma_kernel(
     __bf16 *__restrict__ o, int64_t o_st, int64_t o_sh, float *__restrict__ lse,
     float scale_log2, int total_items, int pairs_per_xcd) {
     __shared__ __attribute__((aligned(16))) unsigned char lds_all[2][2][kTileBytes];   // [group][K, V]
+    LCSA_STAMP(0)
 
     // Workgroups are dealt to the 8 XCDs round-robin; give each XCD a contiguous run of work
     // items (same head, neighbouring tiles, both query frames) so that K/V tiles shared by
@@ -223,6 +251,7 @@ __global__ __launch_bounds__(512, 2) void attn_mfma_kernel(
     stage_barrier();                       // first K tiles of both groups are in LDS
     if (grp8 == 1) { stage_barrier(); stage_barrier(); }   // group 1 runs two phases behind group 0
 
+    LCSA_STAMP(1)
     f16x8 pfrag[8];                        // P^T fragments of the previous block: [key group*2 + k-step]
     uint32_t blk_next = 0;
     bool has_next = false;
@@ -416,6 +445,7 @@ __global__ __launch_bounds__(512, 2) void attn_mfma_kernel(
         __builtin_amdgcn_sched_barrier(0);
     }
     if (grp8 == 0) { stage_barrier(); stage_barrier(); }   // matches group 1's two extra barriers at the start
+    LCSA_STAMP(2)
 
     // ---- epilogue: normalise, transpose through this wavefront's own 8 KB of LDS, store 256-byte rows.
     // No LDS reads of other wavefronts are outstanding: the last stage ended in a barrier.
@@ -450,6 +480,7 @@ __global__ __launch_bounds__(512, 2) void attn_mfma_kernel(
             }
         }
     }
+    LCSA_STAMP(3)
 }
 
 } // namespace

@@ -3,25 +3,12 @@
 // synchronisation, no host<->device copies happen here.
 #include "../../include/lcsa.h"
 #include "lcsa_kernels.h"
+#include "lcsa_cache_handle.h"
 
 #include <new>
 #include <string>
 
 using namespace lcsa;
-
-struct lcsa_cache {
-    lcsa_geom geom;
-    KGeom kg;
-    KCache kc;
-    size_t bytes;
-    int start;             // sliding window: ring slot of the oldest visible group as enqueued so far (host mirror of
-                           // the device words in kc.ring; replays of a captured append do not move it)
-    int32_t policy;        // LCSA_EVICT_*
-    int32_t *order;        // device [heads][cap]: visible group -> slot (importance-based policies)
-    float *importance;     // device [heads][cap]: importance of the visible groups, from lcsa_block_importance
-    float *row_group;      // device [heads][n_qb][cap]: scratch of lcsa_block_importance
-    bool scored;           // `importance` was computed since the last append (the scores are used once)
-};
 
 namespace {
 
