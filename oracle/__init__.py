@@ -173,6 +173,32 @@ def attend(q: np.ndarray, k: np.ndarray, v: np.ndarray, g: Geometry, kv_frames: 
     return (o, lse) if with_lse else o
 
 
+def attend_bwd(q: np.ndarray, k: np.ndarray, v: np.ndarray, d_o: np.ndarray, g: Geometry, kv_frames: int,
+               sel_idx: np.ndarray, sel_cnt: np.ndarray, scale: float = 0.0):
+    """Gradients of `attend` with the selection held fixed (Sec. 3.2 "Stage 2": the model is trained with the
+    sparse attention; the discrete top-k choice carries no gradient): given d_o = dL/do, returns
+    (dq [q tokens][heads][d], dk, dv [kv tokens][heads][d]) in float64."""
+    q, d_o = np.ascontiguousarray(q, np.float32), np.ascontiguousarray(d_o, np.float32)     # the two share strides
+    q, qst, qsh = _tokens_view(q)
+    k, kst, ksh = _tokens_view(k)
+    v, vst, vsh = _tokens_view(v)
+    assert (kst, ksh) == (vst, vsh) and k.shape == v.shape and d_o.shape == q.shape and d_o.dtype == np.float32
+    assert q.shape == (g.q_frames * g.tokens_per_frame, g.heads, g.head_dim)
+    assert k.shape == (kv_frames * g.tokens_per_frame, g.heads, g.head_dim)
+    sel_idx = np.ascontiguousarray(sel_idx, np.int32)
+    sel_cnt = np.ascontiguousarray(sel_cnt, np.int32)
+    topk = sel_idx.shape[-1]
+    dq = np.empty(q.shape, np.float64)
+    dk = np.empty(k.shape, np.float64)
+    dv = np.empty(k.shape, np.float64)
+    _load().lcsa_oracle_attend_bwd(_p(q, _f32), _p(d_o, _f32), _cl(qst), _cl(qsh), _p(k, _f32), _p(v, _f32), _cl(kst), _cl(ksh),
+                                   _ci(g.heads), _ci(g.head_dim), _ci(g.q_frames), _ci(kv_frames),
+                                   _ci(g.grid_h), _ci(g.grid_w), _ci(g.tile_t), _ci(g.tile_h), _ci(g.tile_w),
+                                   _p(sel_idx, _i32), _p(sel_cnt, _i32), _ci(topk), _f64(scale),
+                                   _p(dq, _f64), _p(dk, _f64), _p(dv, _f64))
+    return dq, dk, dv
+
+
 def attend_weights(q, k, v, g: Geometry, kv_frames: int, blocks, head: int, q_tok: int, scale: float = 0.0):
     """Softmax weights of one query token over ALL key tokens (zero outside `blocks`) and its output."""
     q, qst, qsh = _tokens_view(q)

@@ -316,6 +316,102 @@ void lcsa_oracle_attend_weights(const float *q, int64_t q_stride_tok, int64_t q_
     free(tok_of);
 }
 
+/* ---- Sec. 3.2 "Stage 2": gradients of the attention on the kept block pairs --------------------------------- */
+
+/*
+ * The model is trained with this sparse attention (Sec. 3.2).  The top-k choice is a discrete decision and carries
+ * no gradient, so the backward pass is that of eq. (1) restricted to the kept pairs: with
+ *   s_ij = scale q_i.k_j,  p_ij = softmax_j(s_ij) over the tokens j of the blocks kept for i's block,  o_i = sum_j p_ij v_j
+ * and an upstream gradient g_i = dL/do_i,
+ *   dv_j += p_ij g_i,   t_ij = g_i.v_j,   D_i = sum_j p_ij t_ij (= g_i.o_i),   u_ij = p_ij (t_ij - D_i),
+ *   dq_i += scale u_ij k_j,   dk_j += scale u_ij q_i.
+ * dq [q tokens][heads][d], dk, dv [kv tokens][heads][d]: dense doubles, written in full (zero where no pair is kept).
+ * q, g share strides; k, v share strides.
+ */
+void lcsa_oracle_attend_bwd(const float *q, const float *g, int64_t q_stride_tok, int64_t q_stride_head,
+                            const float *k, const float *v, int64_t kv_stride_tok, int64_t kv_stride_head,
+                            int heads, int d, int q_frames, int kv_frames,
+                            int H, int W, int tt, int th, int tw,
+                            const int32_t *sel_idx, const int32_t *sel_cnt, int topk, double scale,
+                            double *dq, double *dk, double *dv)
+{
+    const int ty = ceil_div(H, th), tx = ceil_div(W, tw), nb = ty * tx;
+    const int n_qb = (q_frames / tt) * nb;
+    const int64_t n_q = (int64_t)q_frames * H * W, n_kv = (int64_t)kv_frames * H * W;
+    if (scale <= 0.0) scale = 1.0 / sqrt((double)d);
+    memset(dq, 0, sizeof(double) * (size_t)(n_q * heads * d));
+    memset(dk, 0, sizeof(double) * (size_t)(n_kv * heads * d));
+    memset(dv, 0, sizeof(double) * (size_t)(n_kv * heads * d));
+    /* heads are independent (their slices of dk, dv are disjoint); everything inside a head runs in order */
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int h = 0; h < heads; ++h) {
+        const size_t cap = (size_t)topk * tt * th * tw;
+        double *p = (double *)malloc(sizeof(double) * cap);
+        int64_t *tok_of = (int64_t *)malloc(sizeof(int64_t) * cap);
+        for (int qb = 0; qb < n_qb; ++qb) {
+            int grp = qb / nb, t = qb % nb, r0, r1, c0, c1;
+            tile_extent(t / tx, t % tx, H, W, th, tw, &r0, &r1, &c0, &c1);
+            const int32_t *blocks = sel_idx + ((int64_t)h * n_qb + qb) * topk;
+            const int n_blocks = sel_cnt[(int64_t)h * n_qb + qb];
+            for (int f = grp * tt; f < (grp + 1) * tt; ++f)
+                for (int r = r0; r < r1; ++r)
+                    for (int c = c0; c < c1; ++c) {
+                        const int64_t i = ((int64_t)f * H + r) * W + c;
+                        const float *qi = q + i * q_stride_tok + h * q_stride_head;
+                        const float *gi = g + i * q_stride_tok + h * q_stride_head;
+                        /* tokens of the kept blocks and their softmax weights */
+                        int n = 0;
+                        for (int b = 0; b < n_blocks; ++b) {
+                            int kb = blocks[b], kg = kb / nb, kt = kb % nb, kr0, kr1, kc0, kc1;
+                            tile_extent(kt / tx, kt % tx, H, W, th, tw, &kr0, &kr1, &kc0, &kc1);
+                            for (int kf = kg * tt; kf < (kg + 1) * tt; ++kf)
+                                for (int kr = kr0; kr < kr1; ++kr)
+                                    for (int kc = kc0; kc < kc1; ++kc) {
+                                        const int64_t j = ((int64_t)kf * H + kr) * W + kc;
+                                        const float *kj = k + j * kv_stride_tok + h * kv_stride_head;
+                                        double dot = 0.0;
+                                        for (int e = 0; e < d; ++e) dot += (double)qi[e] * (double)kj[e];
+                                        p[n] = dot * scale;
+                                        tok_of[n] = j;
+                                        ++n;
+                                    }
+                        }
+                        if (n == 0) continue;
+                        double mx = p[0];
+                        for (int a = 1; a < n; ++a) if (p[a] > mx) mx = p[a];
+                        double denom = 0.0;
+                        for (int a = 0; a < n; ++a) { p[a] = exp(p[a] - mx); denom += p[a]; }
+                        for (int a = 0; a < n; ++a) p[a] /= denom;
+                        /* D_i = sum_j p_ij (g_i . v_j) */
+                        double D = 0.0;
+                        for (int a = 0; a < n; ++a) {
+                            const float *vj = v + tok_of[a] * kv_stride_tok + h * kv_stride_head;
+                            double tij = 0.0;
+                            for (int e = 0; e < d; ++e) tij += (double)gi[e] * (double)vj[e];
+                            D += p[a] * tij;
+                        }
+                        double *dqi = dq + (i * heads + h) * d;
+                        for (int a = 0; a < n; ++a) {
+                            const int64_t j = tok_of[a];
+                            const float *kj = k + j * kv_stride_tok + h * kv_stride_head;
+                            const float *vj = v + j * kv_stride_tok + h * kv_stride_head;
+                            double tij = 0.0;
+                            for (int e = 0; e < d; ++e) tij += (double)gi[e] * (double)vj[e];
+                            const double u = p[a] * (tij - D);
+                            double *dkj = dk + (j * heads + h) * d, *dvj = dv + (j * heads + h) * d;
+                            for (int e = 0; e < d; ++e) {
+                                dvj[e] += p[a] * (double)gi[e];
+                                dqi[e] += scale * u * (double)kj[e];
+                                dkj[e] += scale * u * (double)qi[e];
+                            }
+                        }
+                    }
+        }
+        free(p);
+        free(tok_of);
+    }
+}
+
 /* Number of OpenMP threads lcsa_oracle_attend will use. */
 #ifdef _OPENMP
 #include <omp.h>

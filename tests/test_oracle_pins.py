@@ -501,3 +501,128 @@ def test_importance_cache_ties_evict_the_older_group_and_new_groups_are_safe():
     c.append(k, v, 4)                                     # two groups arrive, two must go: the tied pair, never the arrivals
     assert c.birth_order().tolist() == [[2, 3, 4]]
     assert c.valid_frames == 6
+
+
+# ---- backward of the attention on the kept pairs (Sec. 3.2 "Stage 2": the model is trained with it) ----------------
+# Pinned against a library routine that shares nothing with the oracle: reverse-mode differentiation (torch
+# autograd, float64) of the textbook masked softmax attention; against central finite differences of the
+# oracle's own forward; and against two identities of eq. (1): the weights of a query sum to one, so the
+# gradient it sends to its keys sums to zero over the keys and the gradient it sends to the values sums to dO.
+
+def autograd_attention_grads(q, k, v, d_o, mask=None, scale=None):
+    import torch
+    tq, tk, tv, tg = (torch.tensor(np.asarray(x, np.float64), requires_grad=r) for x, r in
+                      ((q, True), (k, True), (v, True), (d_o, False)))
+    scale = 1.0 / np.sqrt(q.shape[-1]) if scale is None else scale
+    logits = torch.einsum("ihc,jhc->hij", tq, tk) * scale
+    if mask is not None:
+        logits = logits.masked_fill(~torch.tensor(mask)[None], float("-inf"))
+    o = torch.einsum("hij,jhc->ihc", torch.softmax(logits, dim=-1), tv)
+    (o * tg).sum().backward()
+    return tq.grad.numpy(), tk.grad.numpy(), tv.grad.numpy()
+
+
+@pytest.mark.parametrize("geom,kv_frames", [
+    (Geometry(1, 32, 6, 8, 4, 4, 2, -1, -1, 16), 4),
+    (Geometry(3, 8, 5, 7, 2, 3, 1, -1, -1, 27), 3),
+])
+def test_backward_reduces_to_dense_attention_gradients(geom, kv_frames):
+    rng = np.random.default_rng(41)
+    q, k, v = rand_qkv(rng, geom, kv_frames)
+    d_o = rng.standard_normal(q.shape).astype(np.float32)
+    res = oracle.lcsa(q, k, v, geom, kv_frames)
+    got = oracle.attend_bwd(q, k, v, d_o, geom, kv_frames, res["sel_idx"], res["sel_cnt"])
+    want = autograd_attention_grads(q, k, v, d_o)
+    for a, b, name in zip(got, want, ("dq", "dk", "dv")):
+        np.testing.assert_allclose(a, b, rtol=0, atol=1e-11, err_msg=name)
+
+
+def token_mask_from_selection(g, kv_frames, sel_idx, sel_cnt, head):
+    """mask[q token][k token] of one head, from block ids, written with plain index arithmetic."""
+    ty, tx = -(-g.grid_h // g.tile_h), -(-g.grid_w // g.tile_w)
+    nb, n = ty * tx, g.grid_h * g.grid_w
+
+    def block_of(tok):
+        f, r, c = tok // n, (tok % n) // g.grid_w, tok % g.grid_w
+        return (f // g.tile_t) * nb + (r // g.tile_h) * tx + c // g.tile_w
+    qb = np.array([block_of(t) for t in range(g.q_frames * n)])
+    kb = np.array([block_of(t) for t in range(kv_frames * n)])
+    mask = np.zeros((len(qb), len(kb)), bool)
+    for b in range(g.q_frames // g.tile_t * nb):
+        mask[np.ix_(qb == b, np.isin(kb, sel_idx[head, b, :sel_cnt[head, b]]))] = True
+    return mask
+
+
+@pytest.mark.parametrize("geom,kv_frames", [
+    (Geometry(2, 8, 12, 16, 4, 4, 2, 4, 4, 2), 3),                         # window bites, top-k far below the window
+    (Geometry(2, 8, 9, 14, 4, 4, 2, 4, 8, 4, window_mode=1, tile_t=2), 4),   # two-frame blocks, clipped tiles, preserved window
+])
+def test_backward_of_sparse_attention_matches_autograd_with_the_selection_as_a_mask(geom, kv_frames):
+    rng = np.random.default_rng(42)
+    q, k, v = rand_qkv(rng, geom, kv_frames)
+    d_o = rng.standard_normal(q.shape).astype(np.float32)
+    res = oracle.lcsa(q, k, v, geom, kv_frames)
+    assert (res["sel_cnt"] < kv_frames // geom.tile_t * geom.nb).all()
+    dq, dk, dv = oracle.attend_bwd(q, k, v, d_o, geom, kv_frames, res["sel_idx"], res["sel_cnt"])
+    for h in range(geom.heads):
+        mask = token_mask_from_selection(geom, kv_frames, res["sel_idx"], res["sel_cnt"], h)
+        want = autograd_attention_grads(q[:, h:h + 1], k[:, h:h + 1], v[:, h:h + 1], d_o[:, h:h + 1], mask)
+        for a, b, name in zip((dq, dk, dv), want, ("dq", "dk", "dv")):
+            np.testing.assert_allclose(a[:, h:h + 1], b, rtol=0, atol=1e-11, err_msg=f"{name} head {h}")
+    # key tokens of blocks that nobody kept receive exactly nothing
+    seen = 0
+    for h in range(geom.heads):
+        untouched = ~token_mask_from_selection(geom, kv_frames, res["sel_idx"], res["sel_cnt"], h).any(axis=0)
+        seen += int(untouched.sum())
+        assert (dk[untouched, h] == 0).all() and (dv[untouched, h] == 0).all()
+    assert seen > 0 or geom.topk > 2
+
+
+def test_backward_agrees_with_finite_differences_of_the_forward():
+    g = Geometry(1, 4, 6, 6, 4, 4, 1, 4, 4, 2)
+    kv_frames = 2
+    rng = np.random.default_rng(43)
+    q, k, v = rand_qkv(rng, g, kv_frames)
+    d_o = rng.standard_normal(q.shape).astype(np.float32)
+    sel = oracle.lcsa(q, k, v, g, kv_frames)
+    dq, dk, dv = oracle.attend_bwd(q, k, v, d_o, g, kv_frames, sel["sel_idx"], sel["sel_cnt"], scale=0.7)
+
+    def loss(q_, k_, v_):
+        return float((oracle.attend(q_, k_, v_, g, kv_frames, sel["sel_idx"], sel["sel_cnt"], scale=0.7) * d_o).sum())
+    eps = 2.0 ** -7                           # exactly representable steps keep float32 inputs exact
+    for arr, grad, which in ((q, dq, 0), (k, dk, 1), (v, dv, 2)):
+        for _ in range(12):
+            idx = tuple(int(rng.integers(s)) for s in arr.shape)
+            hi, lo = arr.copy(), arr.copy()
+            hi[idx] += eps
+            lo[idx] -= eps
+            args_hi, args_lo = [q, k, v], [q, k, v]
+            args_hi[which], args_lo[which] = hi, lo
+            fd = (loss(*args_hi) - loss(*args_lo)) / (2 * eps)
+            assert abs(fd - grad[idx]) < 5e-4 * max(1.0, abs(fd)), (which, idx, fd, grad[idx])
+
+
+def test_backward_identities_of_the_softmax():
+    g = Geometry(2, 8, 10, 12, 4, 4, 2, 4, 4, 3)
+    kv_frames = 4
+    rng = np.random.default_rng(44)
+    q, k, v = rand_qkv(rng, g, kv_frames)
+    d_o = rng.standard_normal(q.shape).astype(np.float32)
+    sel = oracle.lcsa(q, k, v, g, kv_frames)
+    dq, dk, dv = oracle.attend_bwd(q, k, v, d_o, g, kv_frames, sel["sel_idx"], sel["sel_cnt"])
+    # sum_j p_ij = 1: the value gradients add up to the upstream gradients, per head and channel
+    np.testing.assert_allclose(dv.sum(axis=0), d_o.astype(np.float64).sum(axis=0), rtol=0, atol=1e-10)
+    # sum_j u_ij = 0 and dk_j = scale sum_i u_ij q_i: with all queries equal the key gradients cancel over the keys
+    q_same = np.broadcast_to(q[:1], q.shape).copy()
+    _, dk2, _ = oracle.attend_bwd(q_same, k, v, d_o, g, kv_frames, sel["sel_idx"], sel["sel_cnt"])
+    np.testing.assert_allclose(dk2.sum(axis=0), 0.0, atol=1e-10)
+    # o does not change when every key moves by the same vector (the logits of a query all shift alike),
+    # so dq is orthogonal to nothing in particular but dL along that direction is zero: sum_j dk_j . u = 0 for
+    # any u only in the equal-queries case above; for general queries check the directional derivative instead
+    u = rng.standard_normal(g.head_dim)
+    direction = float((dk * u[None, None, :]).sum())
+    contrib = np.einsum("ihc,c->ih", q.astype(np.float64), u)       # every query's logits shift by scale q_i.u: no effect
+    assert abs(direction) < 1e-9 * (1 + np.abs(contrib).sum())
+    # constant V: o = c whatever the weights, so no gradient reaches q or k
+    dq3, dk3, _ = oracle.attend_bwd(q, k, np.full_like(v, 0.5), d_o, g, kv_frames, sel["sel_idx"], sel["sel_cnt"])
+    assert np.abs(dq3).max() < 1e-12 and np.abs(dk3).max() < 1e-12
