@@ -236,6 +236,33 @@ int32_t lcsa_sparse_attn_fwd(const lcsa_geom *geom,
                              void *o, int64_t o_stride_tok, int64_t o_stride_head,
                              float *lse, float scale, void *stream);
 
+/* ---- backward of the block-sparse attention (Sec. 3.2 "Stage 2": the model is trained with it) --------- */
+
+/*
+ * Gradients of lcsa_sparse_attn_fwd with respect to q, k and v, the selection held fixed: the top-k choice is a
+ * discrete decision and carries no gradient, so this is the backward of eq. (1) over the kept block pairs.
+ *   q, d_o      device, geom->dtype, raster order over the chunk's q_frames frames, each with its own strides;
+ *               d_o is the gradient of the loss with respect to the forward's output
+ *   k, v        device, geom->dtype, raster order over the kv_frames frames that were visible at the forward,
+ *               oldest first (the order key-block ids count in), shared strides; kv_frames a multiple of tile_t.
+ *               They are read from these tensors, not from a cache: no cache is needed for a backward
+ *   sel_idx, sel_cnt   as given to the forward;   lse: device float [token][head] as written by the forward
+ *   d_q         device float [q_frames*grid_h*grid_w][heads][head_dim], contiguous
+ *   d_k, d_v    device float [kv_frames*grid_h*grid_w][heads][head_dim], contiguous
+ *   delta       device float [q_frames*grid_h*grid_w][heads]: receives D_i = sum_j p_ij (d_o_i . v_j), the quantity
+ *               usually taken as d_o_i . o_i; it is formed from the kernel's own probabilities instead, because the
+ *               forward's output rounded to bf16 would put a relative error of several 1e-3 into d_q and d_k
+ * All results are written in full (zeros where no kept pair reaches).  scale <= 0 selects 1/sqrt(head_dim).
+ * Float arithmetic throughout, fixed summation orders (reproducible bit for bit).
+ * LCSA_EUNSUPPORTED if 2 * (tokens per block) * head_dim floats (a key block's accumulators) exceed the LDS.
+ */
+int32_t lcsa_sparse_attn_bwd(const lcsa_geom *geom,
+                             const void *q, int64_t q_stride_tok, int64_t q_stride_head,
+                             const void *k, const void *v, int64_t kv_stride_tok, int64_t kv_stride_head, int32_t kv_frames,
+                             const int32_t *sel_idx, const int32_t *sel_cnt,
+                             const void *d_o, int64_t o_stride_tok, int64_t o_stride_head, const float *lse,
+                             float *d_q, float *d_k, float *d_v, float *delta, float scale, void *stream);
+
 /* Static, human-readable text for a status code. */
 const char *lcsa_status_string(int32_t status);
 /* Text of the last HIP error seen by this thread's most recent LCSA_EHIP ("" if none). */

@@ -97,6 +97,8 @@ def lib():
         L.lcsa_pool_blocks.argtypes = [_gp, _vp, _i64, _i64, _i32, _vp, _vp]
         L.lcsa_select_blocks.argtypes = [_gp, _vp, _vp, _vp, _vp, _vp, _vp]
         L.lcsa_sparse_attn_fwd.argtypes = [_gp, _vp, _i64, _i64, _vp, _vp, _vp, _vp, _i64, _i64, _vp, _f32, _vp]
+        L.lcsa_sparse_attn_bwd.argtypes = [_gp, _vp, _i64, _i64, _vp, _vp, _i64, _i64, _i32, _vp, _vp, _vp, _i64, _i64, _vp,
+                                           _vp, _vp, _vp, _vp, _f32, _vp]
         L.lcsa_cache_v_clamped_device.argtypes = [_vp]
         L.lcsa_cache_v_clamped_device.restype = _vp
         L.lcsa_pool_select_blocks.argtypes = [_gp, _vp, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _vp]
@@ -113,7 +115,7 @@ def lib():
         L.lcsa_last_hip_error.restype = ctypes.c_char_p
         for f in ("lcsa_cache_init", "lcsa_cache_reset", "lcsa_cache_valid_frames", "lcsa_cache_frame_slot",
                   "lcsa_kv_cache_append", "lcsa_pool_blocks", "lcsa_select_blocks", "lcsa_sparse_attn_fwd",
-                  "lcsa_pool_select_blocks", "lcsa_cache_set_eviction", "lcsa_cache_eviction", "lcsa_block_importance",
+                  "lcsa_pool_select_blocks", "lcsa_cache_set_eviction", "lcsa_cache_eviction", "lcsa_block_importance", "lcsa_sparse_attn_bwd",
                   "lcsa_block_importance_static"):
             getattr(L, f).restype = _i32
         _lib = L
@@ -347,3 +349,32 @@ def lcsa_sparse_attn_fwd(geom: Geom, q: torch.Tensor, cache: Cache, sel_idx: tor
                                       op, ost, osh, lse.data_ptr() if lse is not None else None, scale,
                                       _stream(stream)), "lcsa_sparse_attn_fwd")
     return o
+
+
+def lcsa_sparse_attn_bwd(geom: Geom, q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, kv_frames: int,
+                         sel_idx: torch.Tensor, sel_cnt: torch.Tensor, d_o: torch.Tensor,
+                         lse: torch.Tensor, scale: float = 0.0, stream=None):
+    """Gradients (d_q, d_k, d_v), float32 [tokens][heads][d], of the attention on the kept pairs, and delta [tokens][heads]."""
+    qp, qst, qsh = _tok(q)
+    kp, kst, ksh = _tok(k)
+    vp, vst, vsh = _tok(v)
+    gp, gst, gsh = _tok(d_o)
+    if (kst, ksh) != (vst, vsh):
+        raise LcsaError("lcsa_sparse_attn_bwd: k and v must share strides")
+    n = geom.tokens_per_frame
+    if q.shape != (geom.q_frames * n, geom.heads, geom.head_dim) or k.shape != (kv_frames * n, geom.heads, geom.head_dim) \
+            or v.shape != k.shape or d_o.shape != q.shape:
+        raise LcsaError("lcsa_sparse_attn_bwd: shape mismatch")
+    if any(x.dtype != geom.torch_dtype for x in (q, k, v, d_o)):
+        raise LcsaError("lcsa_sparse_attn_bwd: dtype mismatch")
+    assert lse.is_contiguous() and lse.dtype == torch.float32 and lse.shape == (q.shape[0], geom.heads)
+    assert sel_idx.is_contiguous() and sel_cnt.is_contiguous() and sel_idx.dtype == torch.int32 and sel_cnt.dtype == torch.int32
+    d_q = torch.empty(q.shape, dtype=torch.float32, device=q.device)
+    d_k = torch.empty(k.shape, dtype=torch.float32, device=q.device)
+    d_v = torch.empty(k.shape, dtype=torch.float32, device=q.device)
+    delta = torch.empty(q.shape[0], geom.heads, dtype=torch.float32, device=q.device)
+    g = geom.c()
+    _check(lib().lcsa_sparse_attn_bwd(ctypes.byref(g), qp, qst, qsh, kp, vp, kst, ksh, kv_frames, sel_idx.data_ptr(),
+                                      sel_cnt.data_ptr(), gp, gst, gsh, lse.data_ptr(), d_q.data_ptr(), d_k.data_ptr(),
+                                      d_v.data_ptr(), delta.data_ptr(), scale, _stream(stream)), "lcsa_sparse_attn_bwd")
+    return d_q, d_k, d_v, delta

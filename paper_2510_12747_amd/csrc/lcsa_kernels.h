@@ -129,6 +129,16 @@ hipError_t launch_attn_mfma(const KGeom &g, const KCache &c, const void *q, int6
                             void *o, int64_t o_st, int64_t o_sh, float *lse, float scale,
                             hipStream_t stream);
 
+// Backward of the attention on the kept pairs (selection held fixed): d_q [q tokens][heads][d], d_k, d_v
+// [kv_groups*tt*H*W][heads][d], float, contiguous, written in full.  k, v: raster tensors of the visible frames,
+// oldest first; delta: float [q tokens][heads], receives D_i = sum_j p_ij (dO_i.v_j).  attn_bwd_supported: the key-block accumulators (2 * bt * d floats) must fit in LDS.
+bool attn_bwd_supported(const KGeom &g);
+hipError_t launch_attn_bwd(const KGeom &g, int kv_groups, const void *q, int64_t q_st, int64_t q_sh,
+                           const void *k, const void *v, int64_t kv_st, int64_t kv_sh,
+                           const int32_t *sel_idx, const int32_t *sel_cnt,
+                           const void *d_o, int64_t o_st, int64_t o_sh, const float *lse,
+                           float *d_q, float *d_k, float *d_v, float *delta, float scale, hipStream_t stream);
+
 // Largest number of admissible key blocks of any query block (host arithmetic).
 int max_candidates(const KGeom &g, int valid_groups);
 
