@@ -214,6 +214,39 @@ def attend_weights(q, k, v, g: Geometry, kv_frames: int, blocks, head: int, q_to
     return w, o
 
 
+def default_rope_pairs(head_dim: int):
+    """Channel pairs given to the (frame, row, column) axes when the caller states no split: a third of the
+    pairs to each spatial axis, the rest to the frame axis."""
+    third = head_dim // 6
+    return head_dim // 2 - 2 * third, third, third
+
+
+def rope(x: np.ndarray, g: Geometry, n_frames: int, pairs=None, base: float = 10000.0, first_frame: int = 0) -> np.ndarray:
+    """Rotary position embedding in its relative formulation (RoFormer, which Sec. 3.3 builds its locality argument
+    on), applied per axis of the (frame, row, column) position of a token: the channels of a head are consecutive
+    pairs (2i, 2i+1); the first pairs[0] pairs rotate with the frame index (first_frame + frame within x), the next
+    pairs[1] with the row, the last pairs[2] with the column; pair i of an axis that owns n pairs turns by the
+    angle position * base**(-i/n).  x: [n_frames*H*W][heads][d] -> float64 array of the same shape.  (The paper
+    does not print the layout its backbone uses: the split and the base are parameters, their defaults a reading.)"""
+    pairs = default_rope_pairs(g.head_dim) if pairs is None else tuple(pairs)
+    assert sum(pairs) * 2 == g.head_dim and x.shape == (n_frames * g.tokens_per_frame, g.heads, g.head_dim)
+    out = np.empty(x.shape, np.float64)
+    x = x.astype(np.float64)
+    for tok in range(x.shape[0]):
+        f, rem = divmod(tok, g.tokens_per_frame)
+        r, c = divmod(rem, g.grid_w)
+        pair = 0
+        for pos, n in zip((first_frame + f, r, c), pairs):
+            for i in range(n):
+                angle = pos * base ** (-i / n)
+                cs, sn = np.cos(angle), np.sin(angle)
+                a, b = x[tok, :, 2 * pair], x[tok, :, 2 * pair + 1]
+                out[tok, :, 2 * pair] = a * cs - b * sn
+                out[tok, :, 2 * pair + 1] = a * sn + b * cs
+                pair += 1
+    return out
+
+
 class SlidingWindowCache:
     """KV cache with sliding-window eviction as a plain list of frames
     (appendix "Discussion on Stream VSR Pipelines"; KV-cache eviction appendix:

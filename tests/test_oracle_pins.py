@@ -626,3 +626,57 @@ def test_backward_identities_of_the_softmax():
     # constant V: o = c whatever the weights, so no gradient reaches q or k
     dq3, dk3, _ = oracle.attend_bwd(q, k, np.full_like(v, 0.5), d_o, g, kv_frames, sel["sel_idx"], sel["sel_cnt"])
     assert np.abs(dq3).max() < 1e-12 and np.abs(dk3).max() < 1e-12
+
+
+# ---- rotary position embedding per axis (RoFormer's relative formulation, which Sec. 3.3 argues from) ---------------
+
+def test_rope_is_a_complex_phase_per_pair():
+    """Library routine as the pin: channel pairs as complex numbers times exp(i * angle)."""
+    g = Geometry(2, 12, 3, 5, 2, 2, 2, -1, -1, 1)
+    rng = np.random.default_rng(51)
+    x = rng.standard_normal((2 * 15, 2, 12)).astype(np.float32)
+    pairs, base, first = (2, 1, 3), 100.0, 7
+    got = oracle.rope(x, g, 2, pairs, base, first)
+    z = x.astype(np.float64).reshape(30, 2, 6, 2) @ np.array([1, 1j])          # [tok][head][pair]
+    tok = np.arange(30)
+    pos = np.stack([first + tok // 15, (tok % 15) // 5, tok % 5], axis=1).astype(np.float64)     # frame, row, column
+    angle = np.concatenate([pos[:, a:a + 1] * base ** (-np.arange(n) / n) for a, n in enumerate(pairs)], axis=1)   # [tok][pair]
+    want = z * np.exp(1j * angle)[:, None, :]
+    np.testing.assert_allclose(got[..., 0::2], want.real, atol=1e-13)
+    np.testing.assert_allclose(got[..., 1::2], want.imag, atol=1e-13)
+
+
+def test_rope_hand_values_identity_and_norm():
+    g = Geometry(1, 6, 2, 3, 1, 1, 1, -1, -1, 1)
+    x = np.zeros((6, 1, 6), np.float32)
+    x[:, 0, :] = [1, 0, 0, 2, 3, 4]
+    out = oracle.rope(x, g, 1, (1, 1, 1), 10000.0, 0)
+    np.testing.assert_array_equal(out[0, 0], x[0, 0])                           # frame 0, row 0, column 0: nothing turns
+    # token 4 = row 1, column 1: the row pair (0, 2) and the column pair (3, 4) turn by 1 radian, the frame pair stays
+    c, s = np.cos(1.0), np.sin(1.0)
+    np.testing.assert_allclose(out[4, 0], [1, 0, -2 * s, 2 * c, 3 * c - 4 * s, 3 * s + 4 * c], atol=1e-15)
+    np.testing.assert_allclose((out ** 2).sum(-1), (x.astype(np.float64) ** 2).sum(-1), rtol=1e-14)
+    # second pair of an axis that owns two pairs turns by position * base**(-1/2)
+    g2 = Geometry(1, 4, 1, 9, 1, 1, 1, -1, -1, 1)
+    y = np.zeros((9, 1, 4), np.float32)
+    y[:, 0, 2] = 1.0
+    o2 = oracle.rope(y, g2, 1, (0, 0, 2), 100.0, 0)
+    np.testing.assert_allclose(o2[5, 0, 2:], [np.cos(0.5), np.sin(0.5)], atol=1e-15)          # column 5 * 100**-0.5 = 0.5
+
+
+def test_rope_scores_depend_on_relative_position_only():
+    """The property Sec. 3.3 relies on: <rope(q, m), rope(k, n)> is a function of m - n, per axis."""
+    g = Geometry(1, 12, 4, 6, 1, 1, 1, -1, -1, 1)
+    rng = np.random.default_rng(52)
+    qv, kv = rng.standard_normal(12).astype(np.float32), rng.standard_normal(12).astype(np.float32)
+    q = np.broadcast_to(qv, (24, 1, 12)).copy()
+    k = np.broadcast_to(kv, (24, 1, 12)).copy()
+    dots = []
+    for first in (0, 5):                                                       # the same content, 5 frames later
+        rq, rk = oracle.rope(q, g, 1, None, 10000.0, first), oracle.rope(k, g, 1, None, 10000.0, first)
+        dots.append(np.einsum("ihc,jhc->ij", rq, rk))
+    np.testing.assert_allclose(dots[0], dots[1], atol=1e-12)
+    d = dots[0].reshape(4, 6, 4, 6)                                            # [q row][q col][k row][k col]
+    np.testing.assert_allclose(d[0, 0, 1, 2], d[2, 3, 3, 5], atol=1e-12)       # both: one row down, two columns right
+    np.testing.assert_allclose(d[1, 4, 0, 1], d[3, 5, 2, 2], atol=1e-12)
+    assert abs(d[0, 0, 1, 2] - d[0, 0, 2, 1]) > 1e-3
