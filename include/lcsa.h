@@ -185,6 +185,23 @@ int32_t lcsa_pool_blocks(const lcsa_geom *geom, const void *x,
                          int64_t stride_tok, int64_t stride_head,
                          int32_t n_frames, float *pooled, void *stream);
 
+/*
+ * Rotary position embedding fused with the pooling, for the tensors on their way into this library (Q before
+ * lcsa_select_blocks / lcsa_sparse_attn_fwd, K before lcsa_kv_cache_append): one pass over x instead of two.
+ * Sec. 3.3 rests its local window on the relative formulation of RoPE; the paper does not print the channel
+ * layout of its backbone, so the split is the caller's: the channels of a head are consecutive pairs
+ * (2i, 2i+1); the first pairs_t pairs turn with the frame index first_frame + (frame within x), the next
+ * pairs_h with the row, the last pairs_w with the column (pairs_t + pairs_h + pairs_w = head_dim/2); pair i of
+ * an axis that owns n pairs turns by position * base^(-i/n) (base <= 0 selects 10000).
+ *   x_rot    device, geom->dtype, own strides, may be x itself: the rotated tokens (float arithmetic, rounded
+ *            to the element type)
+ *   pooled   as lcsa_pool_blocks would compute it on x_rot, bit for bit
+ * 0 <= first_frame, first_frame + n_frames <= 2^24.
+ */
+int32_t lcsa_rope_pool_blocks(const lcsa_geom *geom, const void *x, int64_t stride_tok, int64_t stride_head, int32_t n_frames,
+                              int32_t pairs_t, int32_t pairs_h, int32_t pairs_w, float base, int32_t first_frame,
+                              void *x_rot, int64_t rot_stride_tok, int64_t rot_stride_head, float *pooled, void *stream);
+
 /* ---- block selection (Sec. 3.2 coarse map + top-k, Sec. 3.3 / Fig. 3 local window) ----------- */
 
 /*

@@ -95,6 +95,7 @@ def lib():
         L.lcsa_cache_frame_slot.argtypes = [_vp, _i32]
         L.lcsa_kv_cache_append.argtypes = [_vp, _vp, _vp, _i64, _i64, _i32, _vp]
         L.lcsa_pool_blocks.argtypes = [_gp, _vp, _i64, _i64, _i32, _vp, _vp]
+        L.lcsa_rope_pool_blocks.argtypes = [_gp, _vp, _i64, _i64, _i32, _i32, _i32, _i32, _f32, _i32, _vp, _i64, _i64, _vp, _vp]
         L.lcsa_select_blocks.argtypes = [_gp, _vp, _vp, _vp, _vp, _vp, _vp]
         L.lcsa_sparse_attn_fwd.argtypes = [_gp, _vp, _i64, _i64, _vp, _vp, _vp, _vp, _i64, _i64, _vp, _f32, _vp]
         L.lcsa_sparse_attn_bwd.argtypes = [_gp, _vp, _i64, _i64, _vp, _vp, _i64, _i64, _i32, _vp, _vp, _vp, _i64, _i64, _vp,
@@ -115,7 +116,7 @@ def lib():
         L.lcsa_last_hip_error.restype = ctypes.c_char_p
         for f in ("lcsa_cache_init", "lcsa_cache_reset", "lcsa_cache_valid_frames", "lcsa_cache_frame_slot",
                   "lcsa_kv_cache_append", "lcsa_pool_blocks", "lcsa_select_blocks", "lcsa_sparse_attn_fwd",
-                  "lcsa_pool_select_blocks", "lcsa_cache_set_eviction", "lcsa_cache_eviction", "lcsa_block_importance", "lcsa_sparse_attn_bwd",
+                  "lcsa_pool_select_blocks", "lcsa_cache_set_eviction", "lcsa_cache_eviction", "lcsa_block_importance", "lcsa_sparse_attn_bwd", "lcsa_rope_pool_blocks",
                   "lcsa_block_importance_static"):
             getattr(L, f).restype = _i32
         _lib = L
@@ -282,6 +283,26 @@ def lcsa_pool_blocks(geom: Geom, x: torch.Tensor, n_frames: int, pooled: torch.T
     g = geom.c()
     _check(lib().lcsa_pool_blocks(ctypes.byref(g), xp, st, sh, n_frames, pooled.data_ptr(), _stream(stream)), "lcsa_pool_blocks")
     return pooled
+
+
+def lcsa_rope_pool_blocks(geom: Geom, x: torch.Tensor, n_frames: int, pairs, base: float = 0.0, first_frame: int = 0,
+                          x_rot: torch.Tensor | None = None, pooled: torch.Tensor | None = None, stream=None):
+    """Rotary embedding per (frame, row, column) axis + pooling in one pass; returns (x_rot, pooled).  x_rot may be x."""
+    xp, st, sh = _tok(x)
+    if x.dtype != geom.torch_dtype or x.shape != (n_frames * geom.tokens_per_frame, geom.heads, geom.head_dim):
+        raise LcsaError("lcsa_rope_pool_blocks: shape/dtype mismatch")
+    if x_rot is None:
+        x_rot = torch.empty_like(x, memory_format=torch.contiguous_format)
+    rp, rst, rsh = _tok(x_rot)
+    assert x_rot.shape == x.shape and x_rot.dtype == x.dtype
+    n_blocks = n_frames // geom.tile_t * geom.nb
+    if pooled is None:
+        pooled = torch.empty(geom.heads, n_blocks, geom.head_dim, dtype=torch.float32, device=x.device)
+    assert pooled.is_contiguous() and pooled.dtype == torch.float32 and pooled.numel() == geom.heads * n_blocks * geom.head_dim
+    g = geom.c()
+    _check(lib().lcsa_rope_pool_blocks(ctypes.byref(g), xp, st, sh, n_frames, pairs[0], pairs[1], pairs[2], base, first_frame,
+                                       rp, rst, rsh, pooled.data_ptr(), _stream(stream)), "lcsa_rope_pool_blocks")
+    return x_rot, pooled
 
 
 def lcsa_select_blocks(geom: Geom, pooled_q: torch.Tensor, cache: Cache, sel_idx=None, sel_cnt=None, gap=None,

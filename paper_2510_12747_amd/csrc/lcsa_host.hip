@@ -219,6 +219,20 @@ int32_t lcsa_pool_blocks(const lcsa_geom *geom, const void *x, int64_t stride_to
     return hip_status(launch_pool(kg, x, stride_tok, stride_head, n_frames / kg.tt, pooled, (hipStream_t)stream));
 }
 
+int32_t lcsa_rope_pool_blocks(const lcsa_geom *geom, const void *x, int64_t stride_tok, int64_t stride_head, int32_t n_frames,
+                              int32_t pairs_t, int32_t pairs_h, int32_t pairs_w, float base, int32_t first_frame,
+                              void *x_rot, int64_t rot_stride_tok, int64_t rot_stride_head, float *pooled, void *stream) {
+    if (!geom_ok(geom) || !pooled || n_frames < 1 || n_frames % geom->tile_t) return LCSA_EINVAL;
+    KGeom kg = derive(*geom);
+    if (!tensor_ok(x, stride_tok, stride_head, kg) || !tensor_ok(x_rot, rot_stride_tok, rot_stride_head, kg)) return LCSA_EINVAL;
+    if ((int64_t)n_frames * kg.H * kg.W > (1ll << 30)) return LCSA_EINVAL;
+    if (pairs_t < 0 || pairs_h < 0 || pairs_w < 0 || 2 * ((int64_t)pairs_t + pairs_h + pairs_w) != kg.d) return LCSA_EINVAL;
+    if (first_frame < 0 || (int64_t)first_frame + n_frames > (1 << 24)) return LCSA_EINVAL;     // positions are exact in float
+    if (!(base > 0.f)) base = 10000.f;
+    return hip_status(launch_rope_pool(kg, x, stride_tok, stride_head, n_frames / kg.tt, pairs_t, pairs_h, base, first_frame,
+                                       x_rot, rot_stride_tok, rot_stride_head, pooled, (hipStream_t)stream));
+}
+
 int32_t lcsa_select_blocks(const lcsa_geom *geom, const float *pooled_q, const lcsa_cache *cache,
                            int32_t *sel_idx, int32_t *sel_cnt, float *gap, void *stream) {
     if (!geom_ok(geom) || !cache || !pooled_q || !sel_idx || !sel_cnt) return LCSA_EINVAL;

@@ -82,6 +82,12 @@ __host__ __device__ inline int64_t raster_token(const KGeom &g, int group, int f
 hipError_t launch_pool(const KGeom &g, const void *x, int64_t stride_tok, int64_t stride_head,
                        int n_groups, float *pooled, hipStream_t stream);
 
+// Rotary position embedding per (frame, row, column) axis + block pooling of the rotated tokens in one pass;
+// pairs_t + pairs_h + pairs_w = d/2 channel pairs; x_rot may be x itself.
+hipError_t launch_rope_pool(const KGeom &g, const void *x, int64_t st, int64_t sh, int n_groups,
+                            int pairs_t, int pairs_h, float base, int first_frame,
+                            void *x_rot, int64_t rot_st, int64_t rot_sh, float *pooled, hipStream_t stream);
+
 // Writes n_groups groups of frames: tiles of K, V and pooled K.  Importance-based eviction (c.order set):
 // group i into the slot that c.order gives visible group first + i of each head.  Sliding window (c.order
 // null): into ring slots ring[0].. (mod cap), and the launch advances ring[0] by n_groups once every

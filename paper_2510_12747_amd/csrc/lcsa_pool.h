@@ -58,12 +58,18 @@ __device__ inline void finish_pool(float *red, const float *acc, int rg, int j, 
     }
 }
 
+// What accumulate_block does to a 16-byte vector between loading and summing it: nothing, by default.
+struct NoTransform {
+    __device__ uint4 apply(const uint4 &u, int frame, int row, int col, int64_t token) const { return u; }
+};
+
 // Sums this thread's share of one block of x into acc[VEC]: lanes j cover a token row with 16-byte
 // vectors, rows_par = kThreads / lpr token rows are in flight, 8 rows per lane are requested before any
-// is consumed so that the loads overlap.
-template <int VEC>
+// is consumed so that the loads overlap.  xf may change (and store elsewhere) every vector on its way
+// into the sum; the order of the summation does not depend on it.
+template <int VEC, class X = NoTransform>
 __device__ inline void accumulate_block(const KGeom &g, const TileRef &t, const char *x, int64_t st, int64_t sh, int head,
-                                        int rg, int j, int rows_par, float *acc) {
+                                        int rg, int j, int rows_par, float *acc, const X &xf = X()) {
     constexpr int ELT = 16 / VEC;
     for (int tok0 = rg; tok0 < g.bt; tok0 += 8 * rows_par) {
         uint4 u[8];
@@ -79,6 +85,13 @@ __device__ inline void accumulate_block(const KGeom &g, const TileRef &t, const 
         }
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
+            if constexpr (!__is_same(X, NoTransform)) {
+                const int tok = tok0 + i * rows_par;
+                int ft, r, c;
+                if (block_token(g, tok, t.vh, t.vw, ft, r, c))
+                    u[i] = xf.apply(u[i], t.group * g.tt + ft, t.by * g.th + r, t.bx * g.tw + c,
+                                    raster_token(g, t.group, ft, t.by * g.th + r, t.bx * g.tw + c));
+            }
             float f[VEC];
             Unpack<VEC>::to_float(u[i], f);       // zeros for padding add nothing
 #pragma unroll

@@ -63,6 +63,81 @@ __global__ __launch_bounds__(kThreads) void pool_kernel(KGeom g, const char *x, 
 }
 
 // ---------------------------------------------------------------------------------------------
+// Rotary position embedding fused with the pooling (the producer-side fusion for Q and K): one pass reads x,
+// turns every channel pair (2i, 2i+1) by the angle its axis gives it (RoFormer's relative formulation, per
+// (frame, row, column) axis: pair i of an axis that owns n pairs turns by position * base^(-i/n)), stores the
+// rotated token in the element type and sums the STORED values, in the pooling kernel's order: the means are
+// the bits lcsa_pool_blocks would give on the rotated tensor.  A lane always meets the same channels, so its
+// frequencies are computed once, in double: a streamed video reaches frame indices in the thousands, and an
+// angle of thousands of radians formed in float would be off by 1e-4 and more.  The angle is reduced to
+// [-pi, pi] in double; sine and cosine are then taken in float.
+template <int VEC> struct RopeTransform {
+    double freq[VEC / 2];
+    int axis[VEC / 2];           // 0: frame, 1: row, 2: column
+    char *out;
+    int64_t st, sh;
+    int head, j, first_frame;
+    __device__ uint4 apply(const uint4 &u, int frame, int row, int col, int64_t token) const {
+        float f[VEC];
+        Unpack<VEC>::to_float(u, f);
+#pragma unroll
+        for (int p = 0; p < VEC / 2; ++p) {
+            const int pos = axis[p] == 0 ? first_frame + frame : axis[p] == 1 ? row : col;
+            double angle = (double)pos * freq[p];
+            angle -= 6.283185307179586 * rint(angle * 0.15915494309189535);
+            float sn, cs;
+            sincosf((float)angle, &sn, &cs);
+            const float a = f[2 * p], b = f[2 * p + 1];
+            f[2 * p] = a * cs - b * sn;
+            f[2 * p + 1] = a * sn + b * cs;
+        }
+        uint4 r;
+        if constexpr (VEC == 8) {
+            uint32_t w[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                w[i] = (uint32_t)__builtin_bit_cast(unsigned short, (__bf16)f[2 * i]) |
+                       (uint32_t)__builtin_bit_cast(unsigned short, (__bf16)f[2 * i + 1]) << 16;
+            r = make_uint4(w[0], w[1], w[2], w[3]);
+        } else {
+            r = make_uint4(__float_as_uint(f[0]), __float_as_uint(f[1]), __float_as_uint(f[2]), __float_as_uint(f[3]));
+        }
+        *(uint4 *)(out + (token * st + (int64_t)head * sh + j * VEC) * (16 / VEC)) = r;
+        return r;
+    }
+};
+
+template <int VEC>
+__global__ __launch_bounds__(kThreads) void rope_pool_kernel(KGeom g, const char *x, int64_t st, int64_t sh, int n_blocks,
+                                                             int pairs_t, int pairs_h, double log2_base, int first_frame,
+                                                             char *x_rot, int64_t rot_st, int64_t rot_sh, float *pooled) {
+    __shared__ float red[kThreads * VEC];
+    const int block = blockIdx.x / g.heads, head = blockIdx.x - block * g.heads;
+    const TileRef t = tile_ref(g, block);
+    const int lpr = g.d / VEC, rows_par = kThreads / lpr;
+    const int rg = threadIdx.x / lpr, j = threadIdx.x - rg * lpr;
+    const bool active = rg < rows_par;
+    RopeTransform<VEC> xf;
+    const int pairs_w = g.d / 2 - pairs_t - pairs_h;
+#pragma unroll
+    for (int p = 0; p < VEC / 2; ++p) {
+        const int ip = j * (VEC / 2) + p;                    // pair index within the head
+        const int a = ip < pairs_t ? 0 : ip < pairs_t + pairs_h ? 1 : 2;
+        const int i = a == 0 ? ip : a == 1 ? ip - pairs_t : ip - pairs_t - pairs_h;
+        const int n = a == 0 ? pairs_t : a == 1 ? pairs_h : pairs_w;
+        xf.axis[p] = a;
+        xf.freq[p] = exp2(-(double)i / (double)n * log2_base);
+    }
+    xf.out = x_rot; xf.st = rot_st; xf.sh = rot_sh; xf.head = head; xf.j = j; xf.first_frame = first_frame;
+    float acc[VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) acc[e] = 0.f;
+    if (active) accumulate_block<VEC>(g, t, x, st, sh, head, rg, j, rows_par, acc, xf);
+    finish_pool<VEC>(red, acc, rg, j, lpr, rows_par, active, g.d, g.tt * t.vh * t.vw,
+                     pooled + ((int64_t)head * n_blocks + block) * g.d);
+}
+
+// ---------------------------------------------------------------------------------------------
 // Cache append, generic tile image: K and V tiles row-major [bt][d], padded tokens zero;
 // pooled K written beside them.                                      grid n_groups*nb*heads
 template <int VEC>
@@ -224,6 +299,20 @@ hipError_t launch_pool(const KGeom &g, const void *x, int64_t stride_tok, int64_
         pool_kernel<8><<<grid, kThreads, 0, stream>>>(g, (const char *)x, stride_tok, stride_head, n_groups * g.nb, pooled);
     else
         pool_kernel<4><<<grid, kThreads, 0, stream>>>(g, (const char *)x, stride_tok, stride_head, n_groups * g.nb, pooled);
+    return hipGetLastError();
+}
+
+hipError_t launch_rope_pool(const KGeom &g, const void *x, int64_t st, int64_t sh, int n_groups,
+                            int pairs_t, int pairs_h, float base, int first_frame,
+                            void *x_rot, int64_t rot_st, int64_t rot_sh, float *pooled, hipStream_t stream) {
+    dim3 grid(n_groups * g.nb * g.heads);
+    const double log2_base = log2((double)base);
+    if (g.bf16)
+        rope_pool_kernel<8><<<grid, kThreads, 0, stream>>>(g, (const char *)x, st, sh, n_groups * g.nb, pairs_t, pairs_h, log2_base,
+                                                           first_frame, (char *)x_rot, rot_st, rot_sh, pooled);
+    else
+        rope_pool_kernel<4><<<grid, kThreads, 0, stream>>>(g, (const char *)x, st, sh, n_groups * g.nb, pairs_t, pairs_h, log2_base,
+                                                           first_frame, (char *)x_rot, rot_st, rot_sh, pooled);
     return hipGetLastError();
 }
 
