@@ -402,6 +402,17 @@ def trivial_loops(torch, aids):
     pe[1].record()
     torch.cuda.synchronize()
     out["device_copy_gbs"] = round(5 * 2 * float(1 << 30) / (pe[0].elapsed_time(pe[1]) * 1e-3) / 1e9, 1)
+    # the same copy at the size of one paper-scale append (52 MB in, 52 MB out): what a launch of that size can reach
+    n_small = 52 << 20
+    for _ in range(3):
+        cdst[:n_small].copy_(csrc[:n_small])
+    pe[0].record()
+    for _ in range(20):
+        cdst[:n_small].copy_(csrc[:n_small])
+    pe[1].record()
+    torch.cuda.synchronize()
+    out["device_copy_52MB_us"] = round(pe[0].elapsed_time(pe[1]) * 1e3 / 20, 2)
+    out["device_copy_52MB_gbs"] = round(20 * 2 * float(n_small) / (pe[0].elapsed_time(pe[1]) * 1e-3) / 1e9, 1)
     del csrc, cdst
     return out, prop, n_cu
 
