@@ -402,19 +402,81 @@ def trivial_loops(torch, aids):
     pe[1].record()
     torch.cuda.synchronize()
     out["device_copy_gbs"] = round(5 * 2 * float(1 << 30) / (pe[0].elapsed_time(pe[1]) * 1e-3) / 1e9, 1)
-    # the same copy at the size of one paper-scale append (52 MB in, 52 MB out): what a launch of that size can reach
+    # the same copy at the size of one paper-scale append (52 MB in, 52 MB out), over 16 different slices in turn so
+    # that neither side stays in the 256 MB Infinity Cache: what a launch of that size reaches from HBM
     n_small = 52 << 20
-    for _ in range(3):
-        cdst[:n_small].copy_(csrc[:n_small])
+    sl = lambda t, i: t[(i % 16) * n_small:(i % 16 + 1) * n_small]
+    for i in range(4):
+        sl(cdst, i).copy_(sl(csrc, i + 5))
     pe[0].record()
-    for _ in range(20):
-        cdst[:n_small].copy_(csrc[:n_small])
+    for i in range(32):
+        sl(cdst, i).copy_(sl(csrc, i + 5))
     pe[1].record()
     torch.cuda.synchronize()
-    out["device_copy_52MB_us"] = round(pe[0].elapsed_time(pe[1]) * 1e3 / 20, 2)
-    out["device_copy_52MB_gbs"] = round(20 * 2 * float(n_small) / (pe[0].elapsed_time(pe[1]) * 1e-3) / 1e9, 1)
+    out["device_copy_52MB_us"] = round(pe[0].elapsed_time(pe[1]) * 1e3 / 32, 2)
+    out["device_copy_52MB_gbs"] = round(32 * 2 * float(n_small) / (pe[0].elapsed_time(pe[1]) * 1e-3) / 1e9, 1)
     del csrc, cdst
     return out, prop, n_cu
+
+
+def extensions(torch, B, wl):
+    """The calls beside the forward path, timed briefly: the backward of the attention (small-video shape; float
+    FMA kernels, bound by the vector ALU) and the fused rotary embedding + pooling of a paper-scale chunk's
+    queries (bound by HBM)."""
+    out = {}
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    # ---- backward, small-video
+    w = wl.WORKLOADS["small"]
+    g = B.Geom(w.heads, w.head_dim, w.grid_h, w.grid_w, w.tile_h, w.tile_w, w.q_frames, w.cache_frames, w.radius, w.radius,
+               w.topk, dtype=B.LCSA_BF16)
+    s = wl.ChunkStream(w, 0)
+    chunks = [s.next() for _ in range(w.prime_chunks + 1)]
+    dev = lambda x: torch.from_numpy(wl.bf16_bits(x).view(np.int16)).view(torch.bfloat16).cuda()
+    cache = B.lcsa_cache_init(g)
+    for (_, k, v) in chunks:
+        B.lcsa_kv_cache_append(cache, dev(k), dev(v), w.q_frames)
+    qd = dev(chunks[-1][0])
+    K = dev(np.concatenate([c[1] for c in chunks]))
+    V = dev(np.concatenate([c[2] for c in chunks]))
+    _, si, sc, _ = B.lcsa_pool_select_blocks(g, qd, cache, want_gap=False)
+    lse = torch.empty(qd.shape[0], g.heads, dtype=torch.float32, device="cuda")
+    B.lcsa_sparse_attn_fwd(g, qd, cache, si, sc, lse=lse)
+    d_o = torch.randn_like(qd)
+    B.lcsa_sparse_attn_bwd(g, qd, K, V, w.cache_frames, si, sc, d_o, lse)
+    ev[0].record()
+    for _ in range(3):
+        B.lcsa_sparse_attn_bwd(g, qd, K, V, w.cache_frames, si, sc, d_o, lse)
+    ev[1].record()
+    torch.cuda.synchronize()
+    ms = ev[0].elapsed_time(ev[1]) / 3
+    fwd_flop, _ = attention_flop(si, valid_tokens_per_block(w, 1), g.n_qb, g.nb, g.head_dim)
+    flop = fwd_flop * 4.5          # the two kernels form q.k and dO.v twice each (3 + 4 products of the forward's 2, +2 for D)
+    out["sparse_attn_bwd_small_video"] = {"ms": round(ms, 4), "flop_executed": flop, "tflops": round(flop / (ms * 1e-3) / 1e12, 2),
+                                          "roofline": {"bound": "alu", "peak": PEAK_F32_TFLOPS, "unit": "TFLOP/s",
+                                                       "frac": round(flop / (ms * 1e-3) / 1e12 / PEAK_F32_TFLOPS, 4)}}
+    del cache, K, V
+    # ---- rotary embedding + pooling, the queries of a paper-scale chunk
+    w = wl.WORKLOADS["paper"]
+    g = B.Geom(w.heads, w.head_dim, w.grid_h, w.grid_w, w.tile_h, w.tile_w, w.q_frames, w.cache_frames, w.radius, w.radius,
+               w.topk, dtype=B.LCSA_BF16)
+    x = torch.randn(w.q_frames * w.tokens_per_frame, w.heads, w.head_dim, device="cuda").to(torch.bfloat16)
+    xr = torch.empty_like(x)
+    pooled = torch.empty(g.heads, g.n_qb, g.head_dim, dtype=torch.float32, device="cuda")
+    third = g.head_dim // 6
+    pairs = (g.head_dim // 2 - 2 * third, third, third)
+    for _ in range(3):
+        B.lcsa_rope_pool_blocks(g, x, w.q_frames, pairs, 0.0, 7, xr, pooled)
+    ev[0].record()
+    for _ in range(20):
+        B.lcsa_rope_pool_blocks(g, x, w.q_frames, pairs, 0.0, 7, xr, pooled)
+    ev[1].record()
+    torch.cuda.synchronize()
+    ms = ev[0].elapsed_time(ev[1]) / 20
+    nbytes = 2 * x.numel() * 2 + pooled.numel() * 4
+    out["rope_pool_blocks_paper_q"] = {"ms": round(ms, 5), "bytes": nbytes, "gbs": round(nbytes / (ms * 1e-3) / 1e9, 1),
+                                       "roofline": {"bound": "hbm", "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                                                    "frac": round(nbytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)}}
+    return out
 
 
 def main() -> int:
@@ -437,6 +499,7 @@ def main() -> int:
                     help="pool and select with lcsa_pool_blocks + lcsa_select_blocks instead of the fused lcsa_pool_select_blocks")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-others", action="store_true", help="skip the short measurements of the other benchmark configurations")
+    ap.add_argument("--no-streaming", action="store_true", help="skip the chunk-by-chunk stream with its top-k sweep (4k workload)")
     ap.add_argument("--no-aids", action="store_true", help="skip the trivial-loop rates and the kernel time stamps")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device-to-device copy first (reference point for HBM byte counters)")
@@ -486,7 +549,7 @@ def main() -> int:
         "roofline": res["roofline"],
         "setup_s": res["setup_s"],
     }
-    if w.n_chunks > 1:
+    if w.n_chunks > 1 and not args.no_streaming:
         out["streaming"] = streaming_sweep(torch, B, wl, live)
 
     if not args.no_aids:
@@ -533,16 +596,20 @@ def main() -> int:
             if name == args.workload:
                 continue
             torch.cuda.empty_cache()
-            r, lv = measure(torch, B, wl, args, name, steps=5, warmup=2, n_layers=2)
+            # 4 layer calls per step, 4 warm-up and 10 timed steps: shorter runs are dominated by the ramp of the
+            # clocks and read 20 % slow
+            r, lv = measure(torch, B, wl, args, name, steps=10, warmup=4, n_layers=4)
             entry = {"ms_per_chunk_per_layer": round(r["ms_per_layer"], 5), "kernel_ms_per_layer": r["kernel_ms_per_layer"],
                      "hbm_gbs": r["hbm_gbs"],
                      "roofline": {k: r["roofline"][k] for k in ("kernel", "bound", "achieved", "peak", "unit", "frac", "traffic", "avg_launch_ms")},
-                     "layers_per_step": 2, "steps": 5}
+                     "layers_per_step": 4, "steps": 10, "warmup": 4}
             if lv["w"].n_chunks > 1:
                 entry["streaming"] = streaming_sweep(torch, B, wl, lv)
             others[name] = entry
             del lv, r
         out["other_workloads"] = others
+        torch.cuda.empty_cache()
+        out["extensions"] = extensions(torch, B, wl)
     print(json.dumps(out))
     return 0
 
