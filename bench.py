@@ -420,41 +420,49 @@ def trivial_loops(torch, aids):
 
 
 def extensions(torch, B, wl):
-    """The calls beside the forward path, timed briefly: the backward of the attention (small-video shape; float
-    FMA kernels, bound by the vector ALU) and the fused rotary embedding + pooling of a paper-scale chunk's
-    queries (bound by HBM)."""
+    """The calls beside the forward path, timed briefly: the backward of the attention (matrix-core kernels at
+    small-video and paper scale, the float FMA kernels at small-video scale) and the fused rotary embedding +
+    pooling of a paper-scale chunk's queries (bound by HBM)."""
     out = {}
     ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
-    # ---- backward, small-video
-    w = wl.WORKLOADS["small"]
-    g = B.Geom(w.heads, w.head_dim, w.grid_h, w.grid_w, w.tile_h, w.tile_w, w.q_frames, w.cache_frames, w.radius, w.radius,
-               w.topk, dtype=B.LCSA_BF16)
-    s = wl.ChunkStream(w, 0)
-    chunks = [s.next() for _ in range(w.prime_chunks + 1)]
     dev = lambda x: torch.from_numpy(wl.bf16_bits(x).view(np.int16)).view(torch.bfloat16).cuda()
-    cache = B.lcsa_cache_init(g)
-    for (_, k, v) in chunks:
-        B.lcsa_kv_cache_append(cache, dev(k), dev(v), w.q_frames)
-    qd = dev(chunks[-1][0])
-    K = dev(np.concatenate([c[1] for c in chunks]))
-    V = dev(np.concatenate([c[2] for c in chunks]))
-    _, si, sc, _ = B.lcsa_pool_select_blocks(g, qd, cache, want_gap=False)
-    lse = torch.empty(qd.shape[0], g.heads, dtype=torch.float32, device="cuda")
-    B.lcsa_sparse_attn_fwd(g, qd, cache, si, sc, lse=lse)
-    d_o = torch.randn_like(qd)
-    B.lcsa_sparse_attn_bwd(g, qd, K, V, w.cache_frames, si, sc, d_o, lse)
-    ev[0].record()
-    for _ in range(3):
-        B.lcsa_sparse_attn_bwd(g, qd, K, V, w.cache_frames, si, sc, d_o, lse)
-    ev[1].record()
-    torch.cuda.synchronize()
-    ms = ev[0].elapsed_time(ev[1]) / 3
-    fwd_flop, _ = attention_flop(si, valid_tokens_per_block(w, 1), g.n_qb, g.nb, g.head_dim)
-    flop = fwd_flop * 4.5          # the two kernels form q.k and dO.v twice each (3 + 4 products of the forward's 2, +2 for D)
-    out["sparse_attn_bwd_small_video"] = {"ms": round(ms, 4), "flop_executed": flop, "tflops": round(flop / (ms * 1e-3) / 1e12, 2),
-                                          "roofline": {"bound": "alu", "peak": PEAK_F32_TFLOPS, "unit": "TFLOP/s",
-                                                       "frac": round(flop / (ms * 1e-3) / 1e12 / PEAK_F32_TFLOPS, 4)}}
-    del cache, K, V
+    for name in ("small", "paper"):
+        w = wl.WORKLOADS[name]
+        g = B.Geom(w.heads, w.head_dim, w.grid_h, w.grid_w, w.tile_h, w.tile_w, w.q_frames, w.cache_frames, w.radius, w.radius,
+                   w.topk, dtype=B.LCSA_BF16)
+        s = wl.ChunkStream(w, 0)
+        chunks = [s.next() for _ in range(w.prime_chunks + 1)]
+        cache = B.lcsa_cache_init(g)
+        for (_, k, v) in chunks:
+            B.lcsa_kv_cache_append(cache, dev(k), dev(v), w.q_frames)
+        qd = dev(chunks[-1][0])
+        K = dev(np.concatenate([c[1] for c in chunks]))
+        V = dev(np.concatenate([c[2] for c in chunks]))
+        _, si, sc, _ = B.lcsa_pool_select_blocks(g, qd, cache, want_gap=False)
+        lse = torch.empty(qd.shape[0], g.heads, dtype=torch.float32, device="cuda")
+        B.lcsa_sparse_attn_fwd(g, qd, cache, si, sc, lse=lse)
+        d_o = torch.randn_like(qd)
+        fwd_flop, fwd_issued = attention_flop(si, valid_tokens_per_block(w, 1), g.n_qb, g.nb, g.head_dim)
+        for float_path in ((False, True) if name == "small" else (False,)):
+            reps = 3 if float_path else 20
+            for _ in range(2):
+                B.lcsa_sparse_attn_bwd(g, qd, K, V, w.cache_frames, si, sc, d_o, lse, float_path=float_path)
+            ev[0].record()
+            for _ in range(reps):
+                B.lcsa_sparse_attn_bwd(g, qd, K, V, w.cache_frames, si, sc, d_o, lse, float_path=float_path)
+            ev[1].record()
+            torch.cuda.synchronize()
+            ms = ev[0].elapsed_time(ev[1]) / reps
+            # five products where the forward has two (useful: 2.5 x); the kernels execute nine (q.k and dO.v are formed
+            # in the pass that yields D, in the dQ pass and in the dK/dV pass): 4.5 x the forward's executed flop
+            useful, executed = 2.5 * fwd_flop, 4.5 * fwd_issued
+            peak = PEAK_F32_TFLOPS if float_path else PEAK_BF16_TFLOPS
+            out[f"sparse_attn_bwd_{name}_{'float' if float_path else 'matrix_cores'}"] = {
+                "ms": round(ms, 4), "flop_useful": useful, "flop_executed": executed,
+                "useful_tflops": round(useful / (ms * 1e-3) / 1e12, 2),
+                "roofline": {"bound": "alu" if float_path else "mfma", "achieved": round(executed / (ms * 1e-3) / 1e12, 2),
+                             "peak": peak, "unit": "TFLOP/s", "frac": round(executed / (ms * 1e-3) / 1e12 / peak, 4)}}
+        del cache, K, V
     # ---- rotary embedding + pooling, the queries of a paper-scale chunk
     w = wl.WORKLOADS["paper"]
     g = B.Geom(w.heads, w.head_dim, w.grid_h, w.grid_w, w.tile_h, w.tile_w, w.q_frames, w.cache_frames, w.radius, w.radius,

@@ -61,6 +61,8 @@ enum { LCSA_F32 = 0, LCSA_BF16 = 1 };
 enum { LCSA_WINDOW_TRUNCATED = 0, LCSA_WINDOW_PRESERVED = 1 };
 /* KV-cache eviction (appendix on KV-cache eviction): sliding window (the paper's default), or by
  * importance, decided per head or once for all heads of the layer */
+/* arithmetic of lcsa_sparse_attn_bwd: matrix cores where a kernel exists for the shape, or float FMA everywhere */
+enum { LCSA_BWD_AUTO = 0, LCSA_BWD_FLOAT = 1 };
 enum { LCSA_EVICT_SLIDING = 0, LCSA_EVICT_IMPORTANCE_HEADWISE = 1, LCSA_EVICT_IMPORTANCE_UNIFORM = 2 };
 
 /* Problem geometry.  Plain data, passed by pointer, validated on every call. */
@@ -270,15 +272,20 @@ int32_t lcsa_sparse_attn_fwd(const lcsa_geom *geom,
  *               usually taken as d_o_i . o_i; it is formed from the kernel's own probabilities instead, because the
  *               forward's output rounded to bf16 would put a relative error of several 1e-3 into d_q and d_k
  * All results are written in full (zeros where no kept pair reaches).  scale <= 0 selects 1/sqrt(head_dim).
- * Float arithmetic throughout, fixed summation orders (reproducible bit for bit).
- * LCSA_EUNSUPPORTED if 2 * (tokens per block) * head_dim floats (a key block's accumulators) exceed the LDS.
+ * arithmetic = LCSA_BWD_AUTO: for bf16, head_dim 128 and 128-token blocks the products run on the matrix cores (bf16
+ * operands, float accumulation; probabilities and their gradients are rounded to bf16 between the two levels of
+ * products: results within a few 1e-3 of the largest gradient), every other shape in float FMA arithmetic.
+ * LCSA_BWD_FLOAT: float FMA arithmetic for every shape (results within 2e-5 of the largest gradient; slow).
+ * Either way the summation orders are fixed: results are reproducible bit for bit.
+ * The float kernels return LCSA_EUNSUPPORTED if 2 * (tokens per block) * head_dim floats (a key block's
+ * accumulators) exceed the LDS.
  */
 int32_t lcsa_sparse_attn_bwd(const lcsa_geom *geom,
                              const void *q, int64_t q_stride_tok, int64_t q_stride_head,
                              const void *k, const void *v, int64_t kv_stride_tok, int64_t kv_stride_head, int32_t kv_frames,
                              const int32_t *sel_idx, const int32_t *sel_cnt,
                              const void *d_o, int64_t o_stride_tok, int64_t o_stride_head, const float *lse,
-                             float *d_q, float *d_k, float *d_v, float *delta, float scale, void *stream);
+                             float *d_q, float *d_k, float *d_v, float *delta, float scale, int32_t arithmetic, void *stream);
 
 /* Static, human-readable text for a status code. */
 const char *lcsa_status_string(int32_t status);

@@ -18,6 +18,7 @@ LIB_PATH = os.path.join(_HERE, "liblcsa.so")
 
 LCSA_EVICT_SLIDING, LCSA_EVICT_IMPORTANCE_HEADWISE, LCSA_EVICT_IMPORTANCE_UNIFORM = 0, 1, 2
 LCSA_F32, LCSA_BF16 = 0, 1
+LCSA_BWD_AUTO, LCSA_BWD_FLOAT = 0, 1
 WINDOW_TRUNCATED, WINDOW_PRESERVED = 0, 1
 
 
@@ -99,7 +100,7 @@ def lib():
         L.lcsa_select_blocks.argtypes = [_gp, _vp, _vp, _vp, _vp, _vp, _vp]
         L.lcsa_sparse_attn_fwd.argtypes = [_gp, _vp, _i64, _i64, _vp, _vp, _vp, _vp, _i64, _i64, _vp, _f32, _vp]
         L.lcsa_sparse_attn_bwd.argtypes = [_gp, _vp, _i64, _i64, _vp, _vp, _i64, _i64, _i32, _vp, _vp, _vp, _i64, _i64, _vp,
-                                           _vp, _vp, _vp, _vp, _f32, _vp]
+                                           _vp, _vp, _vp, _vp, _f32, _i32, _vp]
         L.lcsa_cache_v_clamped_device.argtypes = [_vp]
         L.lcsa_cache_v_clamped_device.restype = _vp
         L.lcsa_pool_select_blocks.argtypes = [_gp, _vp, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _vp]
@@ -374,8 +375,9 @@ def lcsa_sparse_attn_fwd(geom: Geom, q: torch.Tensor, cache: Cache, sel_idx: tor
 
 def lcsa_sparse_attn_bwd(geom: Geom, q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, kv_frames: int,
                          sel_idx: torch.Tensor, sel_cnt: torch.Tensor, d_o: torch.Tensor,
-                         lse: torch.Tensor, scale: float = 0.0, stream=None):
-    """Gradients (d_q, d_k, d_v), float32 [tokens][heads][d], of the attention on the kept pairs, and delta [tokens][heads]."""
+                         lse: torch.Tensor, scale: float = 0.0, float_path: bool = False, stream=None):
+    """Gradients (d_q, d_k, d_v), float32 [tokens][heads][d], of the attention on the kept pairs, and delta [tokens][heads].
+    float_path: float FMA kernels for every shape (LCSA_BWD_FLOAT) instead of the matrix cores where they apply."""
     qp, qst, qsh = _tok(q)
     kp, kst, ksh = _tok(k)
     vp, vst, vsh = _tok(v)
@@ -397,5 +399,6 @@ def lcsa_sparse_attn_bwd(geom: Geom, q: torch.Tensor, k: torch.Tensor, v: torch.
     g = geom.c()
     _check(lib().lcsa_sparse_attn_bwd(ctypes.byref(g), qp, qst, qsh, kp, vp, kst, ksh, kv_frames, sel_idx.data_ptr(),
                                       sel_cnt.data_ptr(), gp, gst, gsh, lse.data_ptr(), d_q.data_ptr(), d_k.data_ptr(),
-                                      d_v.data_ptr(), delta.data_ptr(), scale, _stream(stream)), "lcsa_sparse_attn_bwd")
+                                      d_v.data_ptr(), delta.data_ptr(), scale, 1 if float_path else 0, _stream(stream)),
+           "lcsa_sparse_attn_bwd")
     return d_q, d_k, d_v, delta

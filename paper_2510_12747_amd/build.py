@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "liblcsa.so")
 SOURCES = ["lcsa_host.hip", "lcsa_pool_append.hip", "lcsa_select.hip", "lcsa_attn_generic.hip", "lcsa_attn_mfma.hip",
-           "lcsa_evict.hip", "lcsa_attn_bwd.hip"]
+           "lcsa_evict.hip", "lcsa_attn_bwd.hip", "lcsa_attn_bwd_mfma.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
          # packed-fp32 VALU forms are kept out of the generated code on purpose
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

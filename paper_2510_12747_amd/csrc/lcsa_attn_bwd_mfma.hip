@@ -1,0 +1,405 @@
+// Backward of the block-sparse attention on the gfx950 matrix cores (bf16, d = 128, 128-token blocks).
+// Same mathematics as lcsa_attn_bwd.hip (selection held fixed; Sec. 3.2 "Stage 2", eq. 1):
+//     p_ij = exp(scale q_i.k_j - lse_i),  t_ij = g_i.v_j,  D_i = sum_j p_ij t_ij,  u_ij = scale p_ij (t_ij - D_i),
+//     dq_i = sum_j u_ij k_j,   dk_j = sum_i u_ij q_i,   dv_j = sum_i p_ij g_i          (g = dL/do)
+// with every product a v_mfma_f32_32x32x16_bf16 (float accumulation); p and u enter the second-level products
+// rounded to bf16, everything else (exponentials, D, the accumulators, the results) is float.  Fixed summation
+// orders, no atomics: results are reproducible bit for bit.
+//
+// Tiles.  A 128 x 128 bf16 tile lives in LDS as 128 rows of 256 bytes, the 16-byte chunk j of row r at chunk
+// position j ^ (r & 15); every matrix operand fragment (32 rows x 8 consecutive elements per half-wave) is then
+// one conflict-free ds_read_b128, whichever of the two operands it feeds.  All five products are of the form
+// C[m][n] = sum_k A[m][k] B[n][k] ("both operands row-major over the summed index"), so besides the token-major
+// image of a tensor tile ([token][channel]) some products need its transpose ([channel][token]): a thread loads an
+// 8-token x 8-channel square (8 x 16 bytes, coalesced along the token rows), and writes it to either image as
+// 8 x 16 bytes, for the transposed one after transposing the square in registers.
+//
+// Operand reuse without LDS round trips: the rows fed to the matrix rows of a first-level product (S or S^T) are
+// permuted (bits 2 and 3 of the row index swapped), which makes the 8 accumulator registers 8s..8s+7 of a lane
+// hold 8 consecutive indices of the summed dimension of the second-level product: the accumulator, rounded to
+// bf16, IS the A operand of that product.
+//
+//   bwd_dq_mfma_kernel    workgroup = (head, query block), wavefront w owns queries 32w..32w+31 (their Q and dO
+//                         fragments stay in registers as B operands).  Pass 1 over the kept key blocks forms
+//                         D_i (stored in `delta`), pass 2 forms u and dQ += u K.  Per key block: K, V and K^T tiles.
+//   bwd_dkv_mfma_kernel   workgroup = (head, key block), wavefront w owns keys 32w..32w+31 (K and V fragments in
+//                         registers).  Walks the query blocks that kept this block (ascending), per query block
+//                         the Q, dO, Q^T and dO^T tiles: dV += P^T dO, dK += U^T Q.
+// The global loads of the next block's squares are requested before the current block is computed.
+#include "lcsa_kernels.h"
+
+#include <type_traits>
+
+namespace lcsa {
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+
+constexpr int kThreads = 256;
+constexpr int kTileBytes = 128 * 256;
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr int kMaxQueryBlocks = 8192;        // flags of the key-block kernel
+
+struct BlockRef { int group, by, bx, vh, vw, n_valid; };
+__device__ inline BlockRef block_ref(const KGeom &g, int block) {
+    BlockRef b;
+    b.group = block / g.nb;
+    const int tile = block - b.group * g.nb;
+    b.by = tile / g.tx;
+    b.bx = tile - b.by * g.tx;
+    b.vh = min(g.th, g.H - b.by * g.th);
+    b.vw = min(g.tw, g.W - b.bx * g.tw);
+    b.n_valid = g.tt * b.vh * b.vw;
+    return b;
+}
+// raster token of the i-th valid token of a block (valid tokens first, in (frame, row, column) order)
+__device__ inline int64_t token_of(const KGeom &g, const BlockRef &b, int i) {
+    int ft, r, c;
+    block_token(g, i, b.vh, b.vw, ft, r, c);
+    return raster_token(g, b.group, ft, b.by * g.th + r, b.bx * g.tw + c);
+}
+
+// byte offset of 16-byte chunk `chunk` of row `row` in a tile image
+__device__ inline int img_off(int row, int chunk) { return row * 256 + ((chunk ^ (row & 15)) << 4); }
+// matrix row m of a first-level product reads tile row swap23(m)
+__device__ inline int swap23(int m) { return (m & 0x13) | ((m & 4) << 1) | ((m & 8) >> 1); }
+
+__device__ inline bf16x8 frag(const unsigned char *img, int row, int chunk) { return *(const bf16x8 *)(img + img_off(row, chunk)); }
+
+// Raster tokens of the eight block tokens 8*tg .. 8*tg+7 of a thread's square (-1 beyond the block's valid tokens):
+// one pair of integer divisions for the first, the others by stepping (column, row, frame) forward.
+__device__ inline void square_tokens(const KGeom &g, const BlockRef &b, int tg, int64_t (&tok)[8]) {
+    const int per_frame = b.vh * b.vw, i0 = 8 * tg;
+    int ft = i0 / per_frame;
+    const int rem = i0 - ft * per_frame;
+    int r = rem / b.vw, c = rem - r * b.vw;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        tok[i] = i0 + i < b.n_valid ? raster_token(g, b.group, ft, b.by * g.th + r, b.bx * g.tw + c) : -1;
+        if (++c == b.vw) { c = 0; if (++r == b.vh) { r = 0; ++ft; } }
+    }
+}
+// this thread's 8-token x 8-channel square of a tile: channels 8*cg .. 8*cg+7 of the tokens above; padding rows are zeros
+__device__ inline void load_square(const int64_t (&tok)[8], const __bf16 *__restrict__ x, int64_t st, int64_t sh, int head, int cg, uint4 (&u)[8]) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        u[i] = make_uint4(0, 0, 0, 0);
+        if (tok[i] >= 0) u[i] = *(const uint4 *)(x + tok[i] * st + (int64_t)head * sh + cg * 8);
+    }
+}
+__device__ inline void store_rows(unsigned char *img, int tg, int cg, const uint4 (&u)[8]) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) *(uint4 *)(img + img_off(8 * tg + i, cg)) = u[i];
+}
+__device__ inline void store_transposed(unsigned char *img, int tg, int cg, const uint4 (&u)[8]) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {                            // channel 8*cg + e of the eight tokens -> one 16-byte chunk of row (channel)
+        uint32_t w[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const uint4 &a = u[2 * i], &b = u[2 * i + 1];
+            const uint32_t wa = e < 2 ? a.x : e < 4 ? a.y : e < 6 ? a.z : a.w;
+            const uint32_t wb = e < 2 ? b.x : e < 4 ? b.y : e < 6 ? b.z : b.w;
+            const uint32_t lo = (e & 1) ? wa >> 16 : wa & 0xffffu, hi = (e & 1) ? wb >> 16 : wb & 0xffffu;
+            w[i] = lo | (hi << 16);
+        }
+        *(uint4 *)(img + img_off(8 * cg + e, tg)) = make_uint4(w[0], w[1], w[2], w[3]);
+    }
+}
+
+// B-operand fragments of the 32 rows a wavefront owns, straight from the raster tensor: lane (n, half) holds
+// x[token(first + n)][16 ks + 8 half .. + 8] for ks = 0..7; rows beyond the block's valid tokens are zeros
+__device__ inline void load_own_rows(const KGeom &g, const BlockRef &b, const __bf16 *__restrict__ x, int64_t st, int64_t sh, int head,
+                                     int first, int lane, bf16x8 (&f)[8]) {
+    const int n = lane & 31, half = lane >> 5;
+    const bool ok = first + n < b.n_valid;
+    const __bf16 *p = x + (ok ? token_of(g, b, first + n) : 0) * st + (int64_t)head * sh + half * 8;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+        const uint4 u = ok ? *(const uint4 *)(p + ks * 16) : make_uint4(0, 0, 0, 0);
+        f[ks] = __builtin_bit_cast(bf16x8, u);
+    }
+}
+
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() would also wait for the global loads of the
+// next block's squares, which are requested before a block is computed precisely so that they overlap with it.
+__device__ inline void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
+__device__ inline void zero(f32x16 &a) {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) a[i] = 0.f;
+}
+
+// ---------------------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))) void bwd_dq_mfma_kernel(
+    KGeom g, int kv_groups, const __bf16 *__restrict__ q, int64_t q_st, int64_t q_sh,
+    const __bf16 *__restrict__ k, const __bf16 *__restrict__ v, int64_t kv_st, int64_t kv_sh,
+    const int32_t *__restrict__ sel_idx, const int32_t *__restrict__ sel_cnt,
+    const __bf16 *__restrict__ d_o, int64_t o_st, int64_t o_sh, const float *__restrict__ lse,
+    float *__restrict__ d_q, float *__restrict__ delta, float scale) {
+    __shared__ __attribute__((aligned(16))) unsigned char k_img[kTileBytes], v_img[kTileBytes], kt_img[kTileBytes];
+    const int qb = blockIdx.x / g.heads, head = blockIdx.x - qb * g.heads;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int ql = lane & 31, half = lane >> 5;
+    const int tg = tid >> 4, cg = tid & 15;                  // this thread's square of a staged tile
+    const int n_qb = g.q_groups * g.nb;
+    const BlockRef qr = block_ref(g, qb);
+    const int64_t row = (int64_t)head * n_qb + qb;
+    const int cnt = min(max(sel_cnt[row], 0), g.topk);
+    const int32_t *sel = sel_idx + row * g.topk;
+    const float scale_log2 = scale * kLog2e;
+
+    // this wavefront's queries: Q and dO fragments (B operands), lse and the token to write to
+    bf16x8 qf[8], gf[8];
+    load_own_rows(g, qr, q, q_st, q_sh, head, 32 * wave, lane, qf);
+    load_own_rows(g, qr, d_o, o_st, o_sh, head, 32 * wave, lane, gf);
+    const bool q_ok = 32 * wave + ql < qr.n_valid;
+    const int64_t q_token = token_of(g, qr, q_ok ? 32 * wave + ql : 0);
+    // padding queries: an infinite reference makes every probability zero
+    const float l2 = q_ok ? lse[q_token * g.heads + head] * kLog2e : __builtin_inff();
+
+    auto key_block = [&](int b) {
+        return block_ref(g, min(max(sel[b], 0), kv_groups * g.nb - 1));   // ids outside the visible blocks must not become wild addresses
+    };
+    float D = 0.f;
+    f32x16 dq[4];
+#pragma unroll
+    for (int nt = 0; nt < 4; ++nt) zero(dq[nt]);
+
+    // One pass over the kept key blocks.  PASS 0 forms D_i = sum_j p_ij t_ij, PASS 1 forms u and dQ += u K.  The
+    // pass number is a compile-time constant so that the element-wise part carries no branches.
+    auto run_pass = [&](auto pass_tag) {
+        constexpr int PASS = decltype(pass_tag)::value;
+        float dsum = 0.f;
+        uint4 ku[8], vu[8];
+        int64_t tok[8];
+        BlockRef kr = key_block(0);
+        if (cnt > 0) {
+            square_tokens(g, kr, tg, tok);
+            load_square(tok, k, kv_st, kv_sh, head, cg, ku);
+            load_square(tok, v, kv_st, kv_sh, head, cg, vu);
+        }
+        for (int b = 0; b < cnt; ++b) {
+            lds_barrier();                                   // everybody is done with the previous block's tiles
+            store_rows(k_img, tg, cg, ku);
+            store_rows(v_img, tg, cg, vu);
+            if (PASS == 1) store_transposed(kt_img, tg, cg, ku);
+            const int n_keys = kr.n_valid;
+            if (b + 1 < cnt) {                               // next block's squares: requested now, consumed after this block's products
+                kr = key_block(b + 1);
+                square_tokens(g, kr, tg, tok);
+                load_square(tok, k, kv_st, kv_sh, head, cg, ku);
+                load_square(tok, v, kv_st, kv_sh, head, cg, vu);
+            }
+            lds_barrier();
+            for (int mt = 0; mt < 4; ++mt) {                 // 32 keys at a time
+                if (mt * 32 >= n_keys) break;
+                const int arow = mt * 32 + swap23(ql);
+                bf16x8 ka[8], va[8];                         // all operand fragments of the unit are requested before the first product
+#pragma unroll
+                for (int ks = 0; ks < 8; ++ks) { ka[ks] = frag(k_img, arow, 2 * ks + half); va[ks] = frag(v_img, arow, 2 * ks + half); }
+                bf16x8 kb_[8];
+                if (PASS == 1) {
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) kb_[i] = frag(kt_img, (i >> 1) * 32 + ql, mt * 4 + 2 * (i & 1) + half);
+                }
+                __builtin_amdgcn_sched_barrier(0);           // keep the reads ahead of the products (the scheduler would sink each next to its use)
+                f32x16 st_, dpt;
+                zero(st_); zero(dpt);
+#pragma unroll
+                for (int ks = 0; ks < 8; ++ks) {
+                    st_ = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks], qf[ks], st_, 0, 0, 0);
+                    dpt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[ks], gf[ks], dpt, 0, 0, 0);
+                }
+                // lane = query ql; register 8 kk + j = key mt*32 + 16 kk + 8 half + j; keys beyond the block's valid ones
+                // (zero rows of the tiles) must get probability zero: left = valid keys from this lane's first one on
+                const int left = n_keys - (mt * 32 + 8 * half);
+                bf16x8 ua[2];
+#pragma unroll
+                for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) {
+                        const int r = kk * 8 + j;
+                        float p = __builtin_amdgcn_exp2f(fmaf(st_[r], scale_log2, -l2));
+                        p = 16 * kk + j < left ? p : 0.f;
+                        if (PASS == 0) dsum = fmaf(p, dpt[r], dsum);
+                        else ua[kk][j] = (__bf16)(p * (dpt[r] - D) * scale);
+                    }
+                if (PASS == 1) {
+#pragma unroll
+                    for (int nt = 0; nt < 4; ++nt)
+#pragma unroll
+                        for (int kk = 0; kk < 2; ++kk)
+                            dq[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ua[kk], kb_[nt * 2 + kk], dq[nt], 0, 0, 0);
+                }
+            }
+        }
+        return dsum;
+    };
+    {
+        const float dsum = run_pass(std::integral_constant<int, 0>());
+        D = dsum + __shfl_xor(dsum, 32);                     // the two half-waves hold the two halves of a query's keys
+        if (q_ok && half == 0) delta[q_token * g.heads + head] = D;
+    }
+    run_pass(std::integral_constant<int, 1>());
+    // dq tile nt: lane = channel nt*32 + ql, register r = query row 8 (r >> 2) + 4 half + (r & 3) of this wavefront
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const int qi = 32 * wave + 8 * (r >> 2) + 4 * half + (r & 3);
+        if (qi < qr.n_valid) {
+            float *out = d_q + (token_of(g, qr, qi) * g.heads + head) * 128 + ql;
+#pragma unroll
+            for (int nt = 0; nt < 4; ++nt) out[nt * 32] = dq[nt][r];
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))) void bwd_dkv_mfma_kernel(
+    KGeom g, int kv_groups, const __bf16 *__restrict__ q, int64_t q_st, int64_t q_sh,
+    const __bf16 *__restrict__ k, const __bf16 *__restrict__ v, int64_t kv_st, int64_t kv_sh,
+    const int32_t *__restrict__ sel_idx, const int32_t *__restrict__ sel_cnt,
+    const __bf16 *__restrict__ d_o, int64_t o_st, int64_t o_sh, const float *__restrict__ lse, const float *__restrict__ delta,
+    float *__restrict__ d_k, float *__restrict__ d_v, float scale) {
+    __shared__ __attribute__((aligned(16))) unsigned char q_img[kTileBytes], g_img[kTileBytes], qt_img[kTileBytes], gt_img[kTileBytes];
+    __shared__ float l2_s[128], D_s[128];
+    __shared__ unsigned char kept_by[kMaxQueryBlocks];
+    const int kb = blockIdx.x / g.heads, head = blockIdx.x - kb * g.heads;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int ql = lane & 31, half = lane >> 5;
+    const int tg = tid >> 4, cg = tid & 15;
+    const int n_qb = g.q_groups * g.nb;
+    const BlockRef kr = block_ref(g, kb);
+    const float scale_log2 = scale * kLog2e;
+
+    // which query blocks kept this key block?  (ascending id lists: binary search)
+    for (int qb = tid; qb < n_qb; qb += kThreads) {
+        const int64_t row = (int64_t)head * n_qb + qb;
+        const int32_t *sel = sel_idx + row * g.topk;
+        const int c = min(max(sel_cnt[row], 0), g.topk);
+        int lo = 0, hi = c;
+        while (lo < hi) { const int mid = (lo + hi) >> 1; if (sel[mid] < kb) lo = mid + 1; else hi = mid; }
+        kept_by[qb] = lo < c && sel[lo] == kb;
+    }
+    // this wavefront's keys: K and V fragments (B operands of the first-level products)
+    bf16x8 kf[8], vf[8];
+    load_own_rows(g, kr, k, kv_st, kv_sh, head, 32 * wave, lane, kf);
+    load_own_rows(g, kr, v, kv_st, kv_sh, head, 32 * wave, lane, vf);
+    const bool key_ok = 32 * wave + ql < kr.n_valid;
+    f32x16 dk[4], dv[4];
+#pragma unroll
+    for (int nt = 0; nt < 4; ++nt) { zero(dk[nt]); zero(dv[nt]); }
+    __syncthreads();
+
+    auto next_kept = [&](int from) { while (from < n_qb && !kept_by[from]) ++from; return from; };   // uniform
+    int qb = next_kept(0);
+    uint4 qu[8], gu[8];
+    float l2_next = 0.f, D_next = 0.f;
+    auto request = [&](int qb_) {                            // global loads of a query block's squares, lse and D
+        const BlockRef qr = block_ref(g, qb_);
+        int64_t tok[8];
+        square_tokens(g, qr, tg, tok);
+        load_square(tok, q, q_st, q_sh, head, cg, qu);
+        load_square(tok, d_o, o_st, o_sh, head, cg, gu);
+        if (tid < 128) {
+            const bool ok = tid < qr.n_valid;
+            const int64_t token = token_of(g, qr, ok ? tid : 0);
+            l2_next = ok ? lse[token * g.heads + head] * kLog2e : __builtin_inff();   // padding queries: probability zero
+            D_next = ok ? delta[token * g.heads + head] : 0.f;
+        }
+    };
+    if (qb < n_qb) request(qb);
+    while (qb < n_qb) {
+        const int n_queries = block_ref(g, qb).n_valid;
+        lds_barrier();                                       // everybody is done with the previous block's tiles
+        store_rows(q_img, tg, cg, qu);
+        store_rows(g_img, tg, cg, gu);
+        store_transposed(qt_img, tg, cg, qu);
+        store_transposed(gt_img, tg, cg, gu);
+        if (tid < 128) { l2_s[tid] = l2_next; D_s[tid] = D_next; }
+        qb = next_kept(qb + 1);
+        if (qb < n_qb) request(qb);                          // consumed after this block's products
+        lds_barrier();
+        for (int mt = 0; mt < 4; ++mt) {                     // 32 queries at a time
+            if (mt * 32 >= n_queries) break;
+            const int arow = mt * 32 + swap23(ql);
+            bf16x8 qa[8], ga[8];                             // all operand fragments of the unit are requested before the first product
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks) { qa[ks] = frag(q_img, arow, 2 * ks + half); ga[ks] = frag(g_img, arow, 2 * ks + half); }
+            bf16x8 gb[8], qb_[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                gb[i] = frag(gt_img, (i >> 1) * 32 + ql, mt * 4 + 2 * (i & 1) + half);
+                qb_[i] = frag(qt_img, (i >> 1) * 32 + ql, mt * 4 + 2 * (i & 1) + half);
+            }
+            __builtin_amdgcn_sched_barrier(0);               // keep the reads ahead of the products (the scheduler would sink each next to its use)
+            f32x16 s, dp;
+            zero(s); zero(dp);
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks) {
+                s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa[ks], kf[ks], s, 0, 0, 0);
+                dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ga[ks], vf[ks], dp, 0, 0, 0);
+            }
+            // lane = key ql of this wavefront; register 8 kk + j = query mt*32 + 16 kk + 8 half + j
+            bf16x8 pa[2], ua[2];
+#pragma unroll
+            for (int kk = 0; kk < 2; ++kk) {
+                const int q0 = mt * 32 + 16 * kk + 8 * half;
+                const float4 la = *(const float4 *)(l2_s + q0), lb = *(const float4 *)(l2_s + q0 + 4);
+                const float4 da = *(const float4 *)(D_s + q0), db = *(const float4 *)(D_s + q0 + 4);
+                const float l8[8] = {la.x, la.y, la.z, la.w, lb.x, lb.y, lb.z, lb.w};
+                const float d8[8] = {da.x, da.y, da.z, da.w, db.x, db.y, db.z, db.w};
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const int r = kk * 8 + j;
+                    float p = __builtin_amdgcn_exp2f(fmaf(s[r], scale_log2, -l8[j]));
+                    p = key_ok ? p : 0.f;
+                    pa[kk][j] = (__bf16)p;
+                    ua[kk][j] = (__bf16)(p * (dp[r] - d8[j]) * scale);
+                }
+            }
+#pragma unroll
+            for (int nt = 0; nt < 4; ++nt)
+#pragma unroll
+                for (int kk = 0; kk < 2; ++kk) {
+                    dv[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pa[kk], gb[nt * 2 + kk], dv[nt], 0, 0, 0);
+                    dk[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ua[kk], qb_[nt * 2 + kk], dk[nt], 0, 0, 0);
+                }
+        }
+    }
+    // tile nt: lane = channel nt*32 + ql, register r = key row 8 (r >> 2) + 4 half + (r & 3) of this wavefront
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const int ki = 32 * wave + 8 * (r >> 2) + 4 * half + (r & 3);
+        if (ki < kr.n_valid) {
+            const int64_t o = (token_of(g, kr, ki) * g.heads + head) * 128 + ql;
+#pragma unroll
+            for (int nt = 0; nt < 4; ++nt) { d_k[o + nt * 32] = dk[nt][r]; d_v[o + nt * 32] = dv[nt][r]; }
+        }
+    }
+}
+
+} // namespace
+
+bool attn_bwd_mfma_supported(const KGeom &g) {
+    return g.bf16 && g.d == 128 && g.bt == 128 && g.q_groups * g.nb <= kMaxQueryBlocks;
+}
+
+hipError_t launch_attn_bwd_mfma(const KGeom &g, int kv_groups, const void *q, int64_t q_st, int64_t q_sh,
+                                const void *k, const void *v, int64_t kv_st, int64_t kv_sh,
+                                const int32_t *sel_idx, const int32_t *sel_cnt,
+                                const void *d_o, int64_t o_st, int64_t o_sh, const float *lse,
+                                float *d_q, float *d_k, float *d_v, float *delta, float scale, hipStream_t stream) {
+    const dim3 grid_q(g.q_groups * g.nb * g.heads), grid_k(kv_groups * g.nb * g.heads);
+    bwd_dq_mfma_kernel<<<grid_q, kThreads, 0, stream>>>(g, kv_groups, (const __bf16 *)q, q_st, q_sh, (const __bf16 *)k, (const __bf16 *)v,
+                                                        kv_st, kv_sh, sel_idx, sel_cnt, (const __bf16 *)d_o, o_st, o_sh, lse, d_q, delta, scale);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    bwd_dkv_mfma_kernel<<<grid_k, kThreads, 0, stream>>>(g, kv_groups, (const __bf16 *)q, q_st, q_sh, (const __bf16 *)k, (const __bf16 *)v,
+                                                         kv_st, kv_sh, sel_idx, sel_cnt, (const __bf16 *)d_o, o_st, o_sh, lse, delta,
+                                                         d_k, d_v, scale);
+    return hipGetLastError();
+}
+
+} // namespace lcsa

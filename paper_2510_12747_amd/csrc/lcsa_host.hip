@@ -311,8 +311,9 @@ int32_t lcsa_sparse_attn_bwd(const lcsa_geom *geom, const void *q, int64_t q_str
                              const void *k, const void *v, int64_t kv_stride_tok, int64_t kv_stride_head, int32_t kv_frames,
                              const int32_t *sel_idx, const int32_t *sel_cnt,
                              const void *d_o, int64_t o_stride_tok, int64_t o_stride_head, const float *lse,
-                             float *d_q, float *d_k, float *d_v, float *delta, float scale, void *stream) {
+                             float *d_q, float *d_k, float *d_v, float *delta, float scale, int32_t arithmetic, void *stream) {
     if (!geom_ok(geom) || !sel_idx || !sel_cnt || !lse || !d_q || !d_k || !d_v || !delta) return LCSA_EINVAL;
+    if (arithmetic != LCSA_BWD_AUTO && arithmetic != LCSA_BWD_FLOAT) return LCSA_EINVAL;
     KGeom kg = derive(*geom);
     if (kv_frames < geom->q_frames || kv_frames % kg.tt) return LCSA_EINVAL;
     if (!tensor_ok(q, q_stride_tok, q_stride_head, kg) || !tensor_ok(k, kv_stride_tok, kv_stride_head, kg) ||
@@ -320,8 +321,12 @@ int32_t lcsa_sparse_attn_bwd(const lcsa_geom *geom, const void *q, int64_t q_str
         return LCSA_EINVAL;
     const int kv_groups = kv_frames / kg.tt;
     if ((int64_t)kv_frames * kg.H * kg.W > (1ll << 30) || (int64_t)kv_groups * kg.nb * kg.heads > (1ll << 30)) return LCSA_EINVAL;
-    if (!attn_bwd_supported(kg)) return LCSA_EUNSUPPORTED;
     if (!(scale > 0.f)) scale = 1.0f / sqrtf((float)kg.d);
+    if (arithmetic == LCSA_BWD_AUTO && attn_bwd_mfma_supported(kg))
+        return hip_status(launch_attn_bwd_mfma(kg, kv_groups, q, q_stride_tok, q_stride_head, k, v, kv_stride_tok, kv_stride_head,
+                                               sel_idx, sel_cnt, d_o, o_stride_tok, o_stride_head, lse, d_q, d_k, d_v, delta, scale,
+                                               (hipStream_t)stream));
+    if (!attn_bwd_supported(kg)) return LCSA_EUNSUPPORTED;
     return hip_status(launch_attn_bwd(kg, kv_groups, q, q_stride_tok, q_stride_head, k, v, kv_stride_tok, kv_stride_head,
                                       sel_idx, sel_cnt, d_o, o_stride_tok, o_stride_head, lse, d_q, d_k, d_v, delta, scale,
                                       (hipStream_t)stream));

@@ -145,6 +145,15 @@ hipError_t launch_attn_bwd(const KGeom &g, int kv_groups, const void *q, int64_t
                            const void *d_o, int64_t o_st, int64_t o_sh, const float *lse,
                            float *d_q, float *d_k, float *d_v, float *delta, float scale, hipStream_t stream);
 
+// The same on the matrix cores (bf16, d = 128, 128-token blocks, at most 8192 query blocks per chunk): products in
+// bf16 with float accumulation, probabilities and their gradients rounded to bf16 between the two product levels.
+bool attn_bwd_mfma_supported(const KGeom &g);
+hipError_t launch_attn_bwd_mfma(const KGeom &g, int kv_groups, const void *q, int64_t q_st, int64_t q_sh,
+                                const void *k, const void *v, int64_t kv_st, int64_t kv_sh,
+                                const int32_t *sel_idx, const int32_t *sel_cnt,
+                                const void *d_o, int64_t o_st, int64_t o_sh, const float *lse,
+                                float *d_q, float *d_k, float *d_v, float *delta, float scale, hipStream_t stream);
+
 // Largest number of admissible key blocks of any query block (host arithmetic).
 int max_candidates(const KGeom &g, int valid_groups);
 

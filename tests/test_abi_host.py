@@ -129,11 +129,13 @@ def test_host_side_validation_without_gpu():
     L.lcsa_sparse_attn_bwd.restype = ctypes.c_int32
     bwd = lambda kvf=6, q=fake, dq=fake, st=1536: L.lcsa_sparse_attn_bwd(
         ctypes.byref(gc), q, st, 128, fake, fake, 1536, 128, kvf, fake, fake, fake, 1536, 128, fake, dq, fake, fake, fake,
-        ctypes.c_float(0.0), None)
+        ctypes.c_float(0.0), 0, None)
     assert bwd(kvf=1) == -1 and bwd(q=None) == -1 and bwd(dq=None) == -1 and bwd(st=64) == -1
     big_block = B.Geom(**{**PAPER, "tile_h": 16, "tile_w": 32, "head_dim": 256}).c()      # 512 tokens x 256 channels per block
     assert L.lcsa_sparse_attn_bwd(ctypes.byref(big_block), fake, 3072, 256, fake, fake, 3072, 256, 6, fake, fake, fake, 3072, 256,
-                                  fake, fake, fake, fake, fake, ctypes.c_float(0.0), None) == -2
+                                  fake, fake, fake, fake, fake, ctypes.c_float(0.0), 0, None) == -2
+    assert L.lcsa_sparse_attn_bwd(ctypes.byref(gc), fake, 1536, 128, fake, fake, 1536, 128, 6, fake, fake, fake, 1536, 128, fake,
+                                  fake, fake, fake, fake, ctypes.c_float(0.0), 7, None) == -1      # unknown arithmetic
     assert L.lcsa_cache_v_clamped_device(h) is not None
     assert L.lcsa_cache_reset(h) == 0
     assert L.lcsa_cache_reset(None) == -1
