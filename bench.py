@@ -508,6 +508,7 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-others", action="store_true", help="skip the short measurements of the other benchmark configurations")
     ap.add_argument("--no-streaming", action="store_true", help="skip the chunk-by-chunk stream with its top-k sweep (4k workload)")
+    ap.add_argument("--only-extensions", action="store_true", help="time only the calls beside the forward path (backward, fused rotary embedding + pooling)")
     ap.add_argument("--no-aids", action="store_true", help="skip the trivial-loop rates and the kernel time stamps")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device-to-device copy first (reference point for HBM byte counters)")
@@ -525,6 +526,10 @@ def main() -> int:
         return 2
     B.lib()   # fail loudly if the HIP library is not built
     aids = Aids()
+
+    if args.only_extensions:
+        print(json.dumps({"extensions": extensions(torch, B, wl)}))
+        return 0
 
     if args.calibrate_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
