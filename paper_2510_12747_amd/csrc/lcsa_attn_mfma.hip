@@ -145,6 +145,10 @@ __device__ inline uint32_t pack_block(const KGeom &g, const KCache &c, int start
 }
 __device__ inline int block_keys(uint32_t blk) { return (int)(blk >> 24) + 1; }
 
+// SINGLE: one work item per workgroup (group 1 only keeps the barriers company).  A lone group is faster than
+// a group that shares its SIMDs, so a launch with no more work items than compute units spreads over twice as
+// many units this way.
+template <bool SINGLE>
 __global__ __launch_bounds__(512, 2) void attn_mfma_kernel(
     KGeom g, KCache c, const __bf16 *__restrict__ q, int64_t q_st, int64_t q_sh,
     const int32_t *__restrict__ sel_idx, const int32_t *__restrict__ sel_cnt,
@@ -157,7 +161,7 @@ __global__ __launch_bounds__(512, 2) void attn_mfma_kernel(
     // items (same head, neighbouring tiles, both query frames) so that K/V tiles shared by
     // neighbouring windows are found in that XCD's L2.
     const int xcd = blockIdx.x & 7, idx = blockIdx.x >> 3;
-    const int total_pairs = (total_items + 1) >> 1;
+    const int total_pairs = SINGLE ? total_items : (total_items + 1) >> 1;
     const int pair = xcd * pairs_per_xcd + idx;
     if (pair >= total_pairs) return;
 
@@ -175,7 +179,8 @@ __global__ __launch_bounds__(512, 2) void attn_mfma_kernel(
         const int tile = rem / g.q_groups, fq = rem - tile * g.q_groups;   // items ordered (head, tile, group)
         qb = fq * g.nb + tile;
     };
-    const int item = 2 * pair + grp8, other = 2 * pair + (grp8 ^ 1);
+    const int item = SINGLE ? (grp8 == 0 ? pair : total_items) : 2 * pair + grp8;
+    const int other = SINGLE ? (grp8 == 0 ? total_items : pair) : 2 * pair + (grp8 ^ 1);
     const bool active = item < total_items;
     int head = 0, qb = 0, cnt = 0, other_cnt = 0;
     const int start = ring_start(c, g);    // requested together with the counts and ids below
@@ -489,11 +494,21 @@ hipError_t launch_attn_mfma(const KGeom &g, const KCache &c, const void *q, int6
                             const int32_t *sel_idx, const int32_t *sel_cnt,
                             void *o, int64_t o_st, int64_t o_sh, float *lse, float scale, hipStream_t stream) {
     const int total = g.heads * g.nb * g.q_groups;
-    const int pairs = (total + 1) / 2;
-    const int per_xcd = (pairs + 7) / 8;
-    attn_mfma_kernel<<<dim3(per_xcd * 8), 512, 0, stream>>>(g, c, (const __bf16 *)q, q_st, q_sh, sel_idx, sel_cnt,
-                                                            (__bf16 *)o, o_st, o_sh, lse, scale * kLog2e,
-                                                            total, per_xcd);
+    int n_cu = 0, dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) n_cu = 256;
+    if (total <= n_cu) {
+        const int per_xcd = (total + 7) / 8;
+        attn_mfma_kernel<true><<<dim3(per_xcd * 8), 512, 0, stream>>>(g, c, (const __bf16 *)q, q_st, q_sh, sel_idx, sel_cnt,
+                                                                      (__bf16 *)o, o_st, o_sh, lse, scale * kLog2e,
+                                                                      total, per_xcd);
+    } else {
+        const int pairs = (total + 1) / 2;
+        const int per_xcd = (pairs + 7) / 8;
+        attn_mfma_kernel<false><<<dim3(per_xcd * 8), 512, 0, stream>>>(g, c, (const __bf16 *)q, q_st, q_sh, sel_idx, sel_cnt,
+                                                                       (__bf16 *)o, o_st, o_sh, lse, scale * kLog2e,
+                                                                       total, per_xcd);
+    }
     return hipGetLastError();
 }
 

@@ -98,6 +98,30 @@ def test_full_sizes_every_row():
     assert r.rows_checked == 12 * 240
 
 
+def test_long_cache_of_22_frames_sparse_and_dense():
+    """The paper's full-attention comparison keeps ~21 latent frames of history (Table 3 context): a ring of 24
+    frames (22 cached + the chunk) on the paper-scale grid, filled by 12 chunks.  Checked at the paper's sparsity
+    (k = 108 of 864 blocks, 13.6 %), at the benchmark's k = 32, and as dense attention over the whole cache
+    (k = all blocks, no window), which is the configuration the sparse launch is timed against."""
+    w = wl.with_overrides(wl.WORKLOADS["paper"], name="long-cache", heads=4, cache_frames=24, topk=108)
+    g, og = geoms(w)
+    p = Pipeline(w)
+    for _ in range(w.prime_chunks):
+        p.feed()
+    q, qd = p.feed()
+    assert p.model.valid_frames == 24
+    p.check_pooled_k()
+    r = p.step(q, qd, rows=sample_rows(og, 24, seed=1))
+    say(f"22 cached frames, k=108: near-tie rows {r.near_tie_rows}, differs {r.sel_mismatch_rows}, max-abs {r.max_abs:.2e}, mean-abs {r.mean_abs:.2e}")
+    gk, ogk = geoms(w, topk=32)
+    r = p.step(q, qd, rows=sample_rows(ogk, 24, seed=2), g=gk, og=ogk)
+    say(f"22 cached frames, k=32: near-tie rows {r.near_tie_rows}, differs {r.sel_mismatch_rows}, max-abs {r.max_abs:.2e}")
+    gd, ogd = geoms(w, topk=864, radius=-1)
+    r = p.step(q, qd, rows=sample_rows(ogd, 6, seed=3), g=gd, og=ogd)
+    assert r.sel_mismatch_rows == 0
+    say(f"22 cached frames, dense (864 blocks per row): max-abs {r.max_abs:.2e}, mean-abs {r.mean_abs:.2e}")
+
+
 # ---- edge cases and variants -------------------------------------------------------------------
 
 SMALL_MFMA = wl.with_overrides(wl.WORKLOADS["small"], name="edge", heads=3, grid_h=20, grid_w=40, radius=16, topk=6)
