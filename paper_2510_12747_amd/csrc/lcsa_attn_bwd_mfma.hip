@@ -6,13 +6,17 @@
 // rounded to bf16, everything else (exponentials, D, the accumulators, the results) is float.  Fixed summation
 // orders, no atomics: results are reproducible bit for bit.
 //
-// Tiles.  A 128 x 128 bf16 tile lives in LDS as 128 rows of 256 bytes, the 16-byte chunk j of row r at chunk
-// position j ^ (r & 15); every matrix operand fragment (32 rows x 8 consecutive elements per half-wave) is then
-// one conflict-free ds_read_b128, whichever of the two operands it feeds.  All five products are of the form
-// C[m][n] = sum_k A[m][k] B[n][k] ("both operands row-major over the summed index"), so besides the token-major
-// image of a tensor tile ([token][channel]) some products need its transpose ([channel][token]): a thread loads an
-// 8-token x 8-channel square (8 x 16 bytes, coalesced along the token rows), and writes it to either image as
-// 8 x 16 bytes, for the transposed one after transposing the square in registers.
+// Tiles.  A 128-token x 128-channel bf16 tile lives in LDS as 128 rows of 256 bytes, the 16-byte chunk j of row r
+// at chunk position j ^ sw(r), sw(r) = the low four bits of r rotated left by one.  It is copied there straight
+// from the raster tensor by direct-to-LDS loads (a wavefront instruction moves 4 rows: lane t lands at byte 16 t of
+// them and fetches the chunk that belongs there; rows beyond the block's valid tokens fetch zeros), two tiles per
+// step into one of two buffers, so that the next block's tiles arrive while the current block is computed.
+// All products have the form C[m][n] = sum_k A[m][k] B[n][k].  Where the summed index runs along the rows of the
+// tile (first level: over channels), an operand fragment is one ds_read_b128 of a row; where it runs down the
+// columns (second level: over keys or queries), the fragment comes from two transposing reads (ds_read_b64_tr_b16:
+// 16 lanes fetch 4 rows x 16 columns and each receives 4 consecutive rows of one column), so no transposed copy of
+// a tile is ever built.  sw() keeps both kinds of read free of bank conflicts: 16 rows with distinct low bits map
+// to 16 distinct chunk positions, and 4 consecutive rows map to 4 distinct 32-byte positions.
 //
 // Operand reuse without LDS round trips: the rows fed to the matrix rows of a first-level product (S or S^T) are
 // permuted (bits 2 and 3 of the row index swapped), which makes the 8 accumulator registers 8s..8s+7 of a lane
@@ -21,11 +25,10 @@
 //
 //   bwd_dq_mfma_kernel    workgroup = (head, query block), wavefront w owns queries 32w..32w+31 (their Q and dO
 //                         fragments stay in registers as B operands).  Pass 1 over the kept key blocks forms
-//                         D_i (stored in `delta`), pass 2 forms u and dQ += u K.  Per key block: K, V and K^T tiles.
+//                         D_i (stored in `delta`), pass 2 forms u and dQ += u K.  Per key block: the K and V tiles.
 //   bwd_dkv_mfma_kernel   workgroup = (head, key block), wavefront w owns keys 32w..32w+31 (K and V fragments in
 //                         registers).  Walks the query blocks that kept this block (ascending), per query block
-//                         the Q, dO, Q^T and dO^T tiles: dV += P^T dO, dK += U^T Q.
-// The global loads of the next block's squares are requested before the current block is computed.
+//                         the Q and dO tiles: dV += P^T dO, dK += U^T Q.
 #include "lcsa_kernels.h"
 
 #include <type_traits>
@@ -34,12 +37,18 @@ namespace lcsa {
 namespace {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) short i16x4;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 
 constexpr int kThreads = 256;
 constexpr int kTileBytes = 128 * 256;
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr int kMaxQueryBlocks = 8192;        // flags of the key-block kernel
+
+#define LCSA_LDS __attribute__((address_space(3)))
+
+// what padding rows of a tile are copied from
+__device__ __attribute__((aligned(256))) const unsigned char zero_row[256] = {};
 
 struct BlockRef { int group, by, bx, vh, vw, n_valid; };
 __device__ inline BlockRef block_ref(const KGeom &g, int block) {
@@ -53,59 +62,37 @@ __device__ inline BlockRef block_ref(const KGeom &g, int block) {
     b.n_valid = g.tt * b.vh * b.vw;
     return b;
 }
-// raster token of the i-th valid token of a block (valid tokens first, in (frame, row, column) order)
-__device__ inline int64_t token_of(const KGeom &g, const BlockRef &b, int i) {
+// raster token of the first token of a block; token i of the block lies rel_token(i) further on
+__device__ inline int64_t block_origin(const KGeom &g, const BlockRef &b) { return raster_token(g, b.group, 0, b.by * g.th, b.bx * g.tw); }
+// distance, in raster tokens, from a block's first token to its i-th valid token (valid tokens first, in
+// (frame, row, column) order over the block's clipped extent vh x vw); -1 beyond the valid tokens
+__device__ inline int rel_token(const KGeom &g, int vh, int vw, int i) {
     int ft, r, c;
-    block_token(g, i, b.vh, b.vw, ft, r, c);
-    return raster_token(g, b.group, ft, b.by * g.th + r, b.bx * g.tw + c);
+    return block_token(g, i, vh, vw, ft, r, c) ? (ft * g.H + r) * g.W + c : -1;
 }
+__device__ inline int64_t token_of(const KGeom &g, const BlockRef &b, int i) { return block_origin(g, b) + rel_token(g, b.vh, b.vw, i); }
 
-// byte offset of 16-byte chunk `chunk` of row `row` in a tile image
-__device__ inline int img_off(int row, int chunk) { return row * 256 + ((chunk ^ (row & 15)) << 4); }
+// chunk position swizzle of a tile image and the byte offset of 16-byte chunk `chunk` of row `row`
+__device__ inline int sw(int row) { return ((row & 7) << 1) | ((row >> 3) & 1); }
+__device__ inline int img_off(int row, int chunk) { return row * 256 + ((chunk ^ sw(row)) << 4); }
 // matrix row m of a first-level product reads tile row swap23(m)
 __device__ inline int swap23(int m) { return (m & 0x13) | ((m & 4) << 1) | ((m & 8) >> 1); }
 
+// operand fragment along a row: elements 8 chunk .. 8 chunk + 7 of row `row`
 __device__ inline bf16x8 frag(const unsigned char *img, int row, int chunk) { return *(const bf16x8 *)(img + img_off(row, chunk)); }
 
-// Raster tokens of the eight block tokens 8*tg .. 8*tg+7 of a thread's square (-1 beyond the block's valid tokens):
-// one pair of integer divisions for the first, the others by stepping (column, row, frame) forward.
-__device__ inline void square_tokens(const KGeom &g, const BlockRef &b, int tg, int64_t (&tok)[8]) {
-    const int per_frame = b.vh * b.vw, i0 = 8 * tg;
-    int ft = i0 / per_frame;
-    const int rem = i0 - ft * per_frame;
-    int r = rem / b.vw, c = rem - r * b.vw;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        tok[i] = i0 + i < b.n_valid ? raster_token(g, b.group, ft, b.by * g.th + r, b.bx * g.tw + c) : -1;
-        if (++c == b.vw) { c = 0; if (++r == b.vh) { r = 0; ++ft; } }
-    }
-}
-// this thread's 8-token x 8-channel square of a tile: channels 8*cg .. 8*cg+7 of the tokens above; padding rows are zeros
-__device__ inline void load_square(const int64_t (&tok)[8], const __bf16 *__restrict__ x, int64_t st, int64_t sh, int head, int cg, uint4 (&u)[8]) {
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        u[i] = make_uint4(0, 0, 0, 0);
-        if (tok[i] >= 0) u[i] = *(const uint4 *)(x + tok[i] * st + (int64_t)head * sh + cg * 8);
-    }
-}
-__device__ inline void store_rows(unsigned char *img, int tg, int cg, const uint4 (&u)[8]) {
-#pragma unroll
-    for (int i = 0; i < 8; ++i) *(uint4 *)(img + img_off(8 * tg + i, cg)) = u[i];
-}
-__device__ inline void store_transposed(unsigned char *img, int tg, int cg, const uint4 (&u)[8]) {
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {                            // channel 8*cg + e of the eight tokens -> one 16-byte chunk of row (channel)
-        uint32_t w[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const uint4 &a = u[2 * i], &b = u[2 * i + 1];
-            const uint32_t wa = e < 2 ? a.x : e < 4 ? a.y : e < 6 ? a.z : a.w;
-            const uint32_t wb = e < 2 ? b.x : e < 4 ? b.y : e < 6 ? b.z : b.w;
-            const uint32_t lo = (e & 1) ? wa >> 16 : wa & 0xffffu, hi = (e & 1) ? wb >> 16 : wb & 0xffffu;
-            w[i] = lo | (hi << 16);
-        }
-        *(uint4 *)(img + img_off(8 * cg + e, tg)) = make_uint4(w[0], w[1], w[2], w[3]);
-    }
+// Operand fragment down a column.  Lane (n = lane & 31, half = lane >> 5) receives column col0 + n, rows
+// row0 + 8 half .. + 7.  A transposing read serves 16 lanes at a time: lane i of the 16 points at 4 elements of row
+// (first + i / 4), columns (c16 + 4 (i % 4) ..), and receives rows first .. first + 3 of column c16 + i.
+__device__ inline bf16x8 frag_down(const unsigned char *img, int row0, int col0, int lane) {
+    const int i = lane & 15, c16 = col0 + (lane & 16), half = lane >> 5;
+    const int chunk = (c16 >> 3) + ((i >> 1) & 1), sub = (i & 1) * 8;
+    const int ra = row0 + 8 * half + (i >> 2), rb = ra + 4;
+    const i16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LCSA_LDS i16x4 *)(img + img_off(ra, chunk) + sub));
+    const i16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LCSA_LDS i16x4 *)(img + img_off(rb, chunk) + sub));
+    typedef __attribute__((ext_vector_type(8))) short i16x8;
+    const i16x8 both = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+    return __builtin_bit_cast(bf16x8, both);
 }
 
 // B-operand fragments of the 32 rows a wavefront owns, straight from the raster tensor: lane (n, half) holds
@@ -122,9 +109,48 @@ __device__ inline void load_own_rows(const KGeom &g, const BlockRef &b, const __
     }
 }
 
-// Workgroup barrier that orders LDS traffic only.  __syncthreads() would also wait for the global loads of the
-// next block's squares, which are requested before a block is computed precisely so that they overlap with it.
-__device__ inline void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+// ---- tile copies -------------------------------------------------------------------------------------------------
+// A wavefront copies rows 32 wave .. 32 wave + 31 of a tile with 8 instructions; instruction i moves rows
+// 32 wave + 4 i .. + 3, lane t supplying row (t >> 4), chunk position (t & 15).  RowPlan holds, for the 8 rows of a
+// lane, the distance of the row's token from the block's first token (-1: padding row) for one block extent; the
+// plan of the unclipped extent is made once, clipped blocks make their own.
+struct RowPlan { int rel[8]; };
+__device__ inline RowPlan plan_rows(const KGeom &g, int vh, int vw, int wave, int lane) {
+    RowPlan p;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) p.rel[i] = rel_token(g, vh, vw, 32 * wave + 4 * i + (lane >> 4));
+    return p;
+}
+// One copy instruction: 64 lanes x 16 bytes from per-lane addresses to LDS bytes lds_rows + 16 lane.  The load
+// stays in flight (counted by vmcnt) until waited for; nothing else orders it.
+__device__ inline void copy_rows_to_lds(const void *src, uint32_t lds_rows) {
+    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" :: "v"(src), "s"(lds_rows) : "memory", "m0");
+}
+// Copies this wavefront's rows of the tiles of block `b` of two tensors that share strides (K and V, or Q and dO).
+__device__ inline void copy_tiles(const KGeom &g, const BlockRef &b, const RowPlan &full, int wave, int lane,
+                                  const __bf16 *__restrict__ x0, const __bf16 *__restrict__ x1, int64_t st, int64_t sh, int head,
+                                  uint32_t lds0, uint32_t lds1) {
+    RowPlan plan = full;
+    if (b.vh != g.th || b.vw != g.tw) plan = plan_rows(g, b.vh, b.vw, wave, lane);     // workgroup-uniform
+    const int64_t origin = block_origin(g, b);
+    const int slot = lane & 15, q4 = lane >> 4;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int chunk = slot ^ sw(4 * i + q4);             // 32 wave is a multiple of 16: it does not enter sw()
+        const int64_t at = ((origin + plan.rel[i]) * st + (int64_t)head * sh + chunk * 8) * 2;
+        const bool ok = plan.rel[i] >= 0;
+        const void *s0 = ok ? (const void *)((const char *)x0 + at) : (const void *)(zero_row + chunk * 16);
+        const void *s1 = ok ? (const void *)((const char *)x1 + at) : (const void *)(zero_row + chunk * 16);
+        const uint32_t rows = (uint32_t)(32 * wave + 4 * i) * 256;
+        copy_rows_to_lds(s0, lds0 + rows);
+        copy_rows_to_lds(s1, lds1 + rows);
+    }
+}
+__device__ inline uint32_t lds_address(const unsigned char *p) { return (uint32_t)(uintptr_t)((LCSA_LDS unsigned char *)p); }
+
+// all of this wavefront's tile copies have landed; then a workgroup barrier: everybody's have, and everybody is
+// done with the buffer that the next copies will overwrite
+__device__ inline void tiles_ready() { asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 
 __device__ inline void zero(f32x16 &a) {
 #pragma unroll
@@ -138,17 +164,19 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
     const int32_t *__restrict__ sel_idx, const int32_t *__restrict__ sel_cnt,
     const __bf16 *__restrict__ d_o, int64_t o_st, int64_t o_sh, const float *__restrict__ lse,
     float *__restrict__ d_q, float *__restrict__ delta, float scale) {
-    __shared__ __attribute__((aligned(16))) unsigned char k_img[kTileBytes], v_img[kTileBytes], kt_img[kTileBytes];
+    __shared__ __attribute__((aligned(16))) unsigned char img[2][2][kTileBytes];      // [buffer][K, V]
     const int qb = blockIdx.x / g.heads, head = blockIdx.x - qb * g.heads;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int ql = lane & 31, half = lane >> 5;
-    const int tg = tid >> 4, cg = tid & 15;                  // this thread's square of a staged tile
     const int n_qb = g.q_groups * g.nb;
     const BlockRef qr = block_ref(g, qb);
     const int64_t row = (int64_t)head * n_qb + qb;
     const int cnt = min(max(sel_cnt[row], 0), g.topk);
     const int32_t *sel = sel_idx + row * g.topk;
     const float scale_log2 = scale * kLog2e;
+    const uint32_t lds_img = lds_address(&img[0][0][0]);
+    const RowPlan full = plan_rows(g, g.th, g.tw, wave, lane);
 
     // this wavefront's queries: Q and dO fragments (B operands), lse and the token to write to
     bf16x8 qf[8], gf[8];
@@ -162,6 +190,9 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
     auto key_block = [&](int b) {
         return block_ref(g, min(max(sel[b], 0), kv_groups * g.nb - 1));   // ids outside the visible blocks must not become wild addresses
     };
+    auto copy_block = [&](const BlockRef &kr, int buf) {
+        copy_tiles(g, kr, full, wave, lane, k, v, kv_st, kv_sh, head, lds_img + buf * 2 * kTileBytes, lds_img + (buf * 2 + 1) * kTileBytes);
+    };
     float D = 0.f;
     f32x16 dq[4];
 #pragma unroll
@@ -172,27 +203,13 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
     auto run_pass = [&](auto pass_tag) {
         constexpr int PASS = decltype(pass_tag)::value;
         float dsum = 0.f;
-        uint4 ku[8], vu[8];
-        int64_t tok[8];
         BlockRef kr = key_block(0);
-        if (cnt > 0) {
-            square_tokens(g, kr, tg, tok);
-            load_square(tok, k, kv_st, kv_sh, head, cg, ku);
-            load_square(tok, v, kv_st, kv_sh, head, cg, vu);
-        }
+        if (cnt > 0) copy_block(kr, 0);
         for (int b = 0; b < cnt; ++b) {
-            lds_barrier();                                   // everybody is done with the previous block's tiles
-            store_rows(k_img, tg, cg, ku);
-            store_rows(v_img, tg, cg, vu);
-            if (PASS == 1) store_transposed(kt_img, tg, cg, ku);
+            tiles_ready();                                   // block b is in buffer b & 1; nobody reads the other buffer any more
             const int n_keys = kr.n_valid;
-            if (b + 1 < cnt) {                               // next block's squares: requested now, consumed after this block's products
-                kr = key_block(b + 1);
-                square_tokens(g, kr, tg, tok);
-                load_square(tok, k, kv_st, kv_sh, head, cg, ku);
-                load_square(tok, v, kv_st, kv_sh, head, cg, vu);
-            }
-            lds_barrier();
+            if (b + 1 < cnt) { kr = key_block(b + 1); copy_block(kr, (b + 1) & 1); }
+            const unsigned char *k_img = img[b & 1][0], *v_img = img[b & 1][1];
             for (int mt = 0; mt < 4; ++mt) {                 // 32 keys at a time
                 if (mt * 32 >= n_keys) break;
                 const int arow = mt * 32 + swap23(ql);
@@ -202,7 +219,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
                 bf16x8 kb_[8];
                 if (PASS == 1) {
 #pragma unroll
-                    for (int i = 0; i < 8; ++i) kb_[i] = frag(kt_img, (i >> 1) * 32 + ql, mt * 4 + 2 * (i & 1) + half);
+                    for (int i = 0; i < 8; ++i) kb_[i] = frag_down(k_img, mt * 32 + 16 * (i & 1), (i >> 1) * 32, lane);
                 }
                 __builtin_amdgcn_sched_barrier(0);           // keep the reads ahead of the products (the scheduler would sink each next to its use)
                 f32x16 st_, dpt;
@@ -235,6 +252,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
                 }
             }
         }
+        __syncthreads();                                     // the next pass starts over in buffer 0
         return dsum;
     };
     {
@@ -262,16 +280,18 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
     const int32_t *__restrict__ sel_idx, const int32_t *__restrict__ sel_cnt,
     const __bf16 *__restrict__ d_o, int64_t o_st, int64_t o_sh, const float *__restrict__ lse, const float *__restrict__ delta,
     float *__restrict__ d_k, float *__restrict__ d_v, float scale) {
-    __shared__ __attribute__((aligned(16))) unsigned char q_img[kTileBytes], g_img[kTileBytes], qt_img[kTileBytes], gt_img[kTileBytes];
-    __shared__ float l2_s[128], D_s[128];
+    __shared__ __attribute__((aligned(16))) unsigned char img[2][2][kTileBytes];      // [buffer][Q, dO]
+    __shared__ float l2_s[2][128], D_s[2][128];
     __shared__ unsigned char kept_by[kMaxQueryBlocks];
     const int kb = blockIdx.x / g.heads, head = blockIdx.x - kb * g.heads;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int ql = lane & 31, half = lane >> 5;
-    const int tg = tid >> 4, cg = tid & 15;
     const int n_qb = g.q_groups * g.nb;
     const BlockRef kr = block_ref(g, kb);
     const float scale_log2 = scale * kLog2e;
+    const uint32_t lds_img = lds_address(&img[0][0][0]);
+    const RowPlan full = plan_rows(g, g.th, g.tw, wave, lane);
 
     // which query blocks kept this key block?  (ascending id lists: binary search)
     for (int qb = tid; qb < n_qb; qb += kThreads) {
@@ -294,14 +314,10 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
 
     auto next_kept = [&](int from) { while (from < n_qb && !kept_by[from]) ++from; return from; };   // uniform
     int qb = next_kept(0);
-    uint4 qu[8], gu[8];
     float l2_next = 0.f, D_next = 0.f;
-    auto request = [&](int qb_) {                            // global loads of a query block's squares, lse and D
+    auto request = [&](int qb_, int buf) {                   // a query block's tiles, lse and D
         const BlockRef qr = block_ref(g, qb_);
-        int64_t tok[8];
-        square_tokens(g, qr, tg, tok);
-        load_square(tok, q, q_st, q_sh, head, cg, qu);
-        load_square(tok, d_o, o_st, o_sh, head, cg, gu);
+        copy_tiles(g, qr, full, wave, lane, q, d_o, q_st, q_sh, head, lds_img + buf * 2 * kTileBytes, lds_img + (buf * 2 + 1) * kTileBytes);
         if (tid < 128) {
             const bool ok = tid < qr.n_valid;
             const int64_t token = token_of(g, qr, ok ? tid : 0);
@@ -309,18 +325,17 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
             D_next = ok ? delta[token * g.heads + head] : 0.f;
         }
     };
-    if (qb < n_qb) request(qb);
+    int buf = 0;
+    if (qb < n_qb) request(qb, 0);
     while (qb < n_qb) {
         const int n_queries = block_ref(g, qb).n_valid;
-        lds_barrier();                                       // everybody is done with the previous block's tiles
-        store_rows(q_img, tg, cg, qu);
-        store_rows(g_img, tg, cg, gu);
-        store_transposed(qt_img, tg, cg, qu);
-        store_transposed(gt_img, tg, cg, gu);
-        if (tid < 128) { l2_s[tid] = l2_next; D_s[tid] = D_next; }
+        // buffer `buf` of the per-query values was last read two blocks ago, before the previous barrier
+        if (tid < 128) { l2_s[buf][tid] = l2_next; D_s[buf][tid] = D_next; }
+        tiles_ready();
         qb = next_kept(qb + 1);
-        if (qb < n_qb) request(qb);                          // consumed after this block's products
-        lds_barrier();
+        if (qb < n_qb) request(qb, buf ^ 1);                 // lands while this block is computed
+        const unsigned char *q_img = img[buf][0], *g_img = img[buf][1];
+        const float *l2_b = l2_s[buf], *D_b = D_s[buf];
         for (int mt = 0; mt < 4; ++mt) {                     // 32 queries at a time
             if (mt * 32 >= n_queries) break;
             const int arow = mt * 32 + swap23(ql);
@@ -330,8 +345,8 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
             bf16x8 gb[8], qb_[8];
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
-                gb[i] = frag(gt_img, (i >> 1) * 32 + ql, mt * 4 + 2 * (i & 1) + half);
-                qb_[i] = frag(qt_img, (i >> 1) * 32 + ql, mt * 4 + 2 * (i & 1) + half);
+                gb[i] = frag_down(g_img, mt * 32 + 16 * (i & 1), (i >> 1) * 32, lane);
+                qb_[i] = frag_down(q_img, mt * 32 + 16 * (i & 1), (i >> 1) * 32, lane);
             }
             __builtin_amdgcn_sched_barrier(0);               // keep the reads ahead of the products (the scheduler would sink each next to its use)
             f32x16 s, dp;
@@ -346,8 +361,8 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
 #pragma unroll
             for (int kk = 0; kk < 2; ++kk) {
                 const int q0 = mt * 32 + 16 * kk + 8 * half;
-                const float4 la = *(const float4 *)(l2_s + q0), lb = *(const float4 *)(l2_s + q0 + 4);
-                const float4 da = *(const float4 *)(D_s + q0), db = *(const float4 *)(D_s + q0 + 4);
+                const float4 la = *(const float4 *)(l2_b + q0), lb = *(const float4 *)(l2_b + q0 + 4);
+                const float4 da = *(const float4 *)(D_b + q0), db = *(const float4 *)(D_b + q0 + 4);
                 const float l8[8] = {la.x, la.y, la.z, la.w, lb.x, lb.y, lb.z, lb.w};
                 const float d8[8] = {da.x, da.y, da.z, da.w, db.x, db.y, db.z, db.w};
 #pragma unroll
@@ -367,6 +382,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
                     dk[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ua[kk], qb_[nt * 2 + kk], dk[nt], 0, 0, 0);
                 }
         }
+        buf ^= 1;
     }
     // tile nt: lane = channel nt*32 + ql, register r = key row 8 (r >> 2) + 4 half + (r & 3) of this wavefront
 #pragma unroll
