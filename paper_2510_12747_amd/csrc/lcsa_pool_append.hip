@@ -67,29 +67,54 @@ __global__ __launch_bounds__(kThreads) void pool_kernel(KGeom g, const char *x, 
 // turns every channel pair (2i, 2i+1) by the angle its axis gives it (RoFormer's relative formulation, per
 // (frame, row, column) axis: pair i of an axis that owns n pairs turns by position * base^(-i/n)), stores the
 // rotated token in the element type and sums the STORED values, in the pooling kernel's order: the means are
-// the bits lcsa_pool_blocks would give on the rotated tensor.  A lane always meets the same channels, so its
-// frequencies are computed once, in double: a streamed video reaches frame indices in the thousands, and an
-// angle of thousands of radians formed in float would be off by 1e-4 and more.  The angle is reduced to
-// [-pi, pi] in double; sine and cosine are then taken in float.
-template <int VEC> struct RopeTransform {
-    double freq[VEC / 2];
+// the bits lcsa_pool_blocks would give on the rotated tensor.  Frequencies and angles are formed in double: a
+// streamed video reaches frame indices in the thousands, and an angle of thousands of radians formed in float
+// would be off by 1e-4 and more.  The angle is reduced to [-pi, pi] in double; sine and cosine are then taken in float.
+//
+// A block spans tt frames, th rows and tw columns, so its tokens need only pairs_t * tt + pairs_h * th + pairs_w * tw
+// distinct (cosine, sine) values: the workgroup computes that table into LDS once and every vector looks its four
+// (or two) pairs up (TABLE).  A block whose table would exceed kRopeTableMax entries computes each value where it
+// is used, by the same arithmetic: both paths give the same bits.
+constexpr int kRopeTableMax = 4096;
+
+struct RopeParams { int pairs_t, pairs_h, pairs_w, first_frame; double log2_base; };
+
+// (cosine, sine) of pair i (of n on its axis) at position pos
+__device__ inline float2 rope_cos_sin(int i, int n, int pos, double log2_base) {
+    const double freq = exp2(-(double)i / (double)n * log2_base);
+    double angle = (double)pos * freq;
+    angle -= 6.283185307179586 * rint(angle * 0.15915494309189535);
+    float sn, cs;
+    sincosf((float)angle, &sn, &cs);
+    return make_float2(cs, sn);
+}
+
+template <int VEC, bool TABLE> struct RopeTransform {
+    RopeParams rp;
+    const float2 *tab;           // TABLE: [pairs_t][tt], [pairs_h][th], [pairs_w][tw] one after the other
     int axis[VEC / 2];           // 0: frame, 1: row, 2: column
+    int index[VEC / 2];          // pair index on its axis
+    int entry[VEC / 2];          // TABLE: where this pair's positions start in tab
+    int origin[3];               // first frame, row, column of the block
     char *out;
     int64_t st, sh;
-    int head, j, first_frame;
+    int head, j;
     __device__ uint4 apply(const uint4 &u, int frame, int row, int col, int64_t token) const {
         float f[VEC];
         Unpack<VEC>::to_float(u, f);
 #pragma unroll
         for (int p = 0; p < VEC / 2; ++p) {
-            const int pos = axis[p] == 0 ? first_frame + frame : axis[p] == 1 ? row : col;
-            double angle = (double)pos * freq[p];
-            angle -= 6.283185307179586 * rint(angle * 0.15915494309189535);
-            float sn, cs;
-            sincosf((float)angle, &sn, &cs);
+            const int pos = axis[p] == 0 ? frame : axis[p] == 1 ? row : col;
+            float2 cs;
+            if constexpr (TABLE) {
+                cs = tab[entry[p] + pos - origin[axis[p]]];
+            } else {
+                const int n = axis[p] == 0 ? rp.pairs_t : axis[p] == 1 ? rp.pairs_h : rp.pairs_w;
+                cs = rope_cos_sin(index[p], n, pos + (axis[p] == 0 ? rp.first_frame : 0), rp.log2_base);
+            }
             const float a = f[2 * p], b = f[2 * p + 1];
-            f[2 * p] = a * cs - b * sn;
-            f[2 * p + 1] = a * sn + b * cs;
+            f[2 * p] = a * cs.x - b * cs.y;
+            f[2 * p + 1] = a * cs.y + b * cs.x;
         }
         uint4 r;
         if constexpr (VEC == 8) {
@@ -107,28 +132,40 @@ template <int VEC> struct RopeTransform {
     }
 };
 
-template <int VEC>
+template <int VEC, bool TABLE>
 __global__ __launch_bounds__(kThreads) void rope_pool_kernel(KGeom g, const char *x, int64_t st, int64_t sh, int n_blocks,
-                                                             int pairs_t, int pairs_h, double log2_base, int first_frame,
-                                                             char *x_rot, int64_t rot_st, int64_t rot_sh, float *pooled) {
+                                                             RopeParams rp, char *x_rot, int64_t rot_st, int64_t rot_sh, float *pooled) {
     __shared__ float red[kThreads * VEC];
+    extern __shared__ float2 rope_table[];
     const int block = blockIdx.x / g.heads, head = blockIdx.x - block * g.heads;
     const TileRef t = tile_ref(g, block);
     const int lpr = g.d / VEC, rows_par = kThreads / lpr;
     const int rg = threadIdx.x / lpr, j = threadIdx.x - rg * lpr;
     const bool active = rg < rows_par;
-    RopeTransform<VEC> xf;
-    const int pairs_w = g.d / 2 - pairs_t - pairs_h;
+    RopeTransform<VEC, TABLE> xf;
+    xf.rp = rp;
+    xf.tab = rope_table;
+    xf.origin[0] = t.group * g.tt; xf.origin[1] = t.by * g.th; xf.origin[2] = t.bx * g.tw;
+    const int len[3] = {g.tt, g.th, g.tw}, pairs[3] = {rp.pairs_t, rp.pairs_h, rp.pairs_w};
+    const int start[3] = {0, rp.pairs_t * g.tt, rp.pairs_t * g.tt + rp.pairs_h * g.th};
+    if (TABLE) {
+        const int n_entries = start[2] + rp.pairs_w * g.tw;
+        for (int e = threadIdx.x; e < n_entries; e += kThreads) {
+            const int a = e < start[1] ? 0 : e < start[2] ? 1 : 2;
+            const int i = (e - start[a]) / len[a], p = (e - start[a]) - i * len[a];
+            rope_table[e] = rope_cos_sin(i, pairs[a], xf.origin[a] + p + (a == 0 ? rp.first_frame : 0), rp.log2_base);
+        }
+        __syncthreads();
+    }
 #pragma unroll
     for (int p = 0; p < VEC / 2; ++p) {
         const int ip = j * (VEC / 2) + p;                    // pair index within the head
-        const int a = ip < pairs_t ? 0 : ip < pairs_t + pairs_h ? 1 : 2;
-        const int i = a == 0 ? ip : a == 1 ? ip - pairs_t : ip - pairs_t - pairs_h;
-        const int n = a == 0 ? pairs_t : a == 1 ? pairs_h : pairs_w;
+        const int a = ip < rp.pairs_t ? 0 : ip < rp.pairs_t + rp.pairs_h ? 1 : 2;
         xf.axis[p] = a;
-        xf.freq[p] = exp2(-(double)i / (double)n * log2_base);
+        xf.index[p] = a == 0 ? ip : a == 1 ? ip - rp.pairs_t : ip - rp.pairs_t - rp.pairs_h;
+        xf.entry[p] = start[a] + xf.index[p] * len[a];
     }
-    xf.out = x_rot; xf.st = rot_st; xf.sh = rot_sh; xf.head = head; xf.j = j; xf.first_frame = first_frame;
+    xf.out = x_rot; xf.st = rot_st; xf.sh = rot_sh; xf.head = head; xf.j = j;
     float acc[VEC];
 #pragma unroll
     for (int e = 0; e < VEC; ++e) acc[e] = 0.f;
@@ -306,13 +343,17 @@ hipError_t launch_rope_pool(const KGeom &g, const void *x, int64_t st, int64_t s
                             int pairs_t, int pairs_h, float base, int first_frame,
                             void *x_rot, int64_t rot_st, int64_t rot_sh, float *pooled, hipStream_t stream) {
     dim3 grid(n_groups * g.nb * g.heads);
-    const double log2_base = log2((double)base);
-    if (g.bf16)
-        rope_pool_kernel<8><<<grid, kThreads, 0, stream>>>(g, (const char *)x, st, sh, n_groups * g.nb, pairs_t, pairs_h, log2_base,
-                                                           first_frame, (char *)x_rot, rot_st, rot_sh, pooled);
-    else
-        rope_pool_kernel<4><<<grid, kThreads, 0, stream>>>(g, (const char *)x, st, sh, n_groups * g.nb, pairs_t, pairs_h, log2_base,
-                                                           first_frame, (char *)x_rot, rot_st, rot_sh, pooled);
+    const RopeParams rp = {pairs_t, pairs_h, g.d / 2 - pairs_t - pairs_h, first_frame, log2((double)base)};
+    const int n_entries = rp.pairs_t * g.tt + rp.pairs_h * g.th + rp.pairs_w * g.tw;
+    const bool table = n_entries <= kRopeTableMax;
+    const size_t lds = table ? n_entries * sizeof(float2) : 0;
+    const char *in = (const char *)x;
+    char *out = (char *)x_rot;
+    const int n_blocks = n_groups * g.nb;
+    if (g.bf16 && table) rope_pool_kernel<8, true><<<grid, kThreads, lds, stream>>>(g, in, st, sh, n_blocks, rp, out, rot_st, rot_sh, pooled);
+    else if (g.bf16) rope_pool_kernel<8, false><<<grid, kThreads, 0, stream>>>(g, in, st, sh, n_blocks, rp, out, rot_st, rot_sh, pooled);
+    else if (table) rope_pool_kernel<4, true><<<grid, kThreads, lds, stream>>>(g, in, st, sh, n_blocks, rp, out, rot_st, rot_sh, pooled);
+    else rope_pool_kernel<4, false><<<grid, kThreads, 0, stream>>>(g, in, st, sh, n_blocks, rp, out, rot_st, rot_sh, pooled);
     return hipGetLastError();
 }
 

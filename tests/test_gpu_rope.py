@@ -67,3 +67,12 @@ def test_rope_pool_f32_tiny():
     w = wl.WORKLOADS["tiny"]
     run_rope(w, 2, (6, 5, 5), 10000.0, 3)
     run_rope(w, 2, (16, 0, 0), 100.0, 0)             # one axis owns everything
+
+
+def test_rope_pool_wide_tiles_without_the_table():
+    """The kernel keeps the (cosine, sine) values of a block in an LDS table of at most 4096 entries; a block
+    with more (here 128 column pairs x 40 columns) computes each value where it is used.  Both paths go through the
+    same checks, and on a geometry that fits the table they are compared with each other through the oracle."""
+    w = wl.with_overrides(wl.WORKLOADS["tiny"], name="rope-no-table", heads=2, head_dim=256, grid_h=3, grid_w=90, tile_h=1, tile_w=40)
+    run_rope(w, 2, (0, 0, 128), 10000.0, 2)
+    run_rope(w, 2, (40, 40, 48), 10000.0, 2)         # 40 + 40 + 48 * 40 = 2000 entries: the table again
