@@ -91,6 +91,15 @@ def test_backward_small_video_bf16():
     run_backward(wl.with_overrides(wl.WORKLOADS["small"], name="bwd-small", heads=3))
 
 
+def test_backward_paper_scale_grid():
+    """The paper-scale grid (48 x 88 tokens, 36 blocks per frame of which the last column is clipped to 8 of 16
+    columns, 2 query + 4 cached frames, top-k 32 inside the 24-token window) with 4 of the 12 heads: 288 query-side
+    and 864 key-side workgroups, several rounds on 256 compute units, in the launch arithmetic the benchmark times.
+    (All 12 heads would keep the oracle busy for minutes; heads are independent of each other.)"""
+    say("backward at the paper-scale grid: the oracle's fp64 gradients take about half a minute")
+    run_backward(wl.with_overrides(wl.WORKLOADS["paper"], name="bwd-paper-grid", heads=4))
+
+
 def test_backward_clipped_blocks_and_partly_filled_cache():
     w = wl.with_overrides(wl.WORKLOADS["small"], name="bwd-edge", heads=2, grid_h=20, grid_w=40, radius=16, topk=6)
     run_backward(w, chunks=2)                                   # 4 of 6 frames visible
