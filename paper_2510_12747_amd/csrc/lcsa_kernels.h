@@ -73,6 +73,24 @@ __host__ __device__ inline bool block_token(const KGeom &g, int i, int vh, int v
     c = rem - r * vw;
     return i < g.tt * per_frame;
 }
+// block_token for many tokens of one block: the two divisions become multiplications by reciprocals prepared once
+// per block.  q = (i * ceil(2^32 / d)) >> 32 equals i / d for i < 65536 and 2 <= d <= 32768 (a block has at most
+// 1024 tokens); d = 1 is passed through.
+struct BlockTokens {
+    uint32_t m_frame, m_row;
+    int per_frame, vw, n_valid;
+    __device__ BlockTokens(const KGeom &g, int vh, int vw_) : per_frame(vh * vw_), vw(vw_), n_valid(g.tt * vh * vw_) {
+        m_frame = 0xFFFFFFFFu / (uint32_t)per_frame + 1u;
+        m_row = 0xFFFFFFFFu / (uint32_t)vw + 1u;
+    }
+    __device__ bool at(int i, int &ft, int &r, int &c) const {
+        ft = per_frame == 1 ? i : (int)__umulhi((uint32_t)i, m_frame);
+        const int rem = i - ft * per_frame;
+        r = vw == 1 ? rem : (int)__umulhi((uint32_t)rem, m_row);
+        c = rem - r * vw;
+        return i < n_valid;
+    }
+};
 // Raster token index of (group, frame in group, absolute row, absolute col).
 __host__ __device__ inline int64_t raster_token(const KGeom &g, int group, int ft, int row, int col) {
     return ((int64_t)(group * g.tt + ft) * g.H + row) * g.W + col;

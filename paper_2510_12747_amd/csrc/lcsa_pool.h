@@ -71,6 +71,7 @@ template <int VEC, class X = NoTransform>
 __device__ inline void accumulate_block(const KGeom &g, const TileRef &t, const char *x, int64_t st, int64_t sh, int head,
                                         int rg, int j, int rows_par, float *acc, const X &xf = X()) {
     constexpr int ELT = 16 / VEC;
+    const BlockTokens bt(g, t.vh, t.vw);
     for (int tok0 = rg; tok0 < g.bt; tok0 += 8 * rows_par) {
         uint4 u[8];
 #pragma unroll
@@ -78,7 +79,7 @@ __device__ inline void accumulate_block(const KGeom &g, const TileRef &t, const 
             const int tok = tok0 + i * rows_par;
             int ft, r, c;
             u[i] = make_uint4(0, 0, 0, 0);
-            if (block_token(g, tok, t.vh, t.vw, ft, r, c)) {
+            if (bt.at(tok, ft, r, c)) {
                 const int64_t token = raster_token(g, t.group, ft, t.by * g.th + r, t.bx * g.tw + c);
                 u[i] = *(const uint4 *)(x + (token * st + (int64_t)head * sh + j * VEC) * ELT);
             }
@@ -88,7 +89,7 @@ __device__ inline void accumulate_block(const KGeom &g, const TileRef &t, const 
             if constexpr (!__is_same(X, NoTransform)) {
                 const int tok = tok0 + i * rows_par;
                 int ft, r, c;
-                if (block_token(g, tok, t.vh, t.vw, ft, r, c))
+                if (bt.at(tok, ft, r, c))
                     u[i] = xf.apply(u[i], t.group * g.tt + ft, t.by * g.th + r, t.bx * g.tw + c,
                                     raster_token(g, t.group, ft, t.by * g.th + r, t.bx * g.tw + c));
             }

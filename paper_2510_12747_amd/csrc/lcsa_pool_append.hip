@@ -198,10 +198,11 @@ __global__ __launch_bounds__(kThreads) void append_generic_kernel(KGeom g, KCach
 #pragma unroll
     for (int e = 0; e < VEC; ++e) acc[e] = 0.f;
     if (active) {
+        const BlockTokens bt(g, t.vh, t.vw);
         for (int tok = rg; tok < g.bt; tok += rows_par) {
             int ft, r, cc;
             uint4 uk = make_uint4(0, 0, 0, 0), uv = uk;
-            if (block_token(g, tok, t.vh, t.vw, ft, r, cc)) {
+            if (bt.at(tok, ft, r, cc)) {
                 const int64_t token = raster_token(g, t.group, ft, t.by * g.th + r, t.bx * g.tw + cc);
                 const int64_t off = (token * st + (int64_t)head * sh + j * VEC) * ELT;
                 uk = *(const uint4 *)(k + off);
@@ -263,11 +264,12 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(KGeom g, KCache c
         if (use_ring) ring_word = c.ring[0];
     }
     uint4 uk[8], uv[8];
+    const BlockTokens bt(g, t.vh, t.vw);
 #pragma unroll
     for (int it = 0; it < 8; ++it) {
         int ft, r, cc;
         uk[it] = make_uint4(0, 0, 0, 0);
-        if (block_token(g, rg + 16 * it, t.vh, t.vw, ft, r, cc)) {
+        if (bt.at(rg + 16 * it, ft, r, cc)) {
             const int64_t token = raster_token(g, t.group, ft, t.by * g.th + r, t.bx * g.tw + cc);
             uk[it] = *(const uint4 *)(k + (token * st + (int64_t)head * sh + j * 8) * 2);
         }
@@ -276,7 +278,7 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(KGeom g, KCache c
     for (int i = 0; i < 8; ++i) {
         int ft, r, cc;
         uv[i] = make_uint4(0, 0, 0, 0);
-        if (block_token(g, 8 * vc + i, t.vh, t.vw, ft, r, cc)) {
+        if (bt.at(8 * vc + i, ft, r, cc)) {
             const int64_t token = raster_token(g, t.group, ft, t.by * g.th + r, t.bx * g.tw + cc);
             uv[i] = *(const uint4 *)(v + (token * st + (int64_t)head * sh + vj * 8) * 2);
         }
@@ -302,7 +304,18 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(KGeom g, KCache c
         for (int e = 0; e < 8; ++e) acc[e] += f[e];
         *(uint4 *)(kt + tok * 256 + ((j ^ (tok & 15)) << 4)) = uk[it];
     }
-    // V: channel e of this thread's eight tokens -> one 16-byte chunk of row 8vj+e, at chunk position vc ^ (row & 15)
+    // V: channel e of this thread's eight tokens -> one 16-byte chunk of row 8vj+e, at chunk position vc ^ (row & 15).
+    // Whether any value needs clamping (magnitude bits >= 0x4780: 65536 and up, infinities, NaN) is looked at two
+    // values per word first: x + 0x3880 carries into bit 15 exactly then.  Wavefronts that hold none, the usual case,
+    // convert pairs with the packed instruction and skip the per-value range handling.
+    uint32_t big = 0;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const uint32_t w4[4] = {uv[i].x, uv[i].y, uv[i].z, uv[i].w};
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) big |= ((w4[q4] & 0x7fff7fffu) + 0x38803880u) & 0x80008000u;
+    }
+    const bool plain = __ballot(big != 0) == 0;                // wavefront-uniform
     int clamped = 0;
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
@@ -313,8 +326,15 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(KGeom g, KCache c
             const uint4 &a = uv[2 * i], &b = uv[2 * i + 1];
             const uint32_t wa = e < 2 ? a.x : e < 4 ? a.y : e < 6 ? a.z : a.w;
             const uint32_t wb = e < 2 ? b.x : e < 4 ? b.y : e < 6 ? b.z : b.w;
-            const uint32_t lo = (e & 1) ? wa >> 16 : wa & 0xffffu, hi = (e & 1) ? wb >> 16 : wb & 0xffffu;
-            w[i] = bf16_bits_to_half_bits(lo, clamped) | (bf16_bits_to_half_bits(hi, clamped) << 16);
+            if (plain) {
+                typedef __attribute__((ext_vector_type(2))) float f32x2;
+                typedef __attribute__((ext_vector_type(2))) _Float16 f16x2;
+                const f32x2 f = {__uint_as_float((e & 1) ? wa & 0xffff0000u : wa << 16), __uint_as_float((e & 1) ? wb & 0xffff0000u : wb << 16)};
+                w[i] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f, f16x2));
+            } else {
+                const uint32_t lo = (e & 1) ? wa >> 16 : wa & 0xffffu, hi = (e & 1) ? wb >> 16 : wb & 0xffffu;
+                w[i] = bf16_bits_to_half_bits(lo, clamped) | (bf16_bits_to_half_bits(hi, clamped) << 16);
+            }
         }
         *(uint4 *)(vt + dd * 256 + ((vc ^ (dd & 15)) << 4)) = make_uint4(w[0], w[1], w[2], w[3]);
     }
