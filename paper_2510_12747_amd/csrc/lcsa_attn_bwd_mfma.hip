@@ -471,33 +471,17 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
         const unsigned char *q_img = img[buf][0], *g_img = img[buf][1];
         const float *l2_b = l2_s[buf], *D_b = D_s[buf];
         const int n_units = (n_queries + 31) >> 5;           // 32-query units that hold valid queries
-        bf16x8 qa[8], ga[8];
+        // Software pipeline over the units (a wavefront has its SIMD to itself): the element-wise work of unit mt
+        // runs beside the second-level products of unit mt - 1:
+        //     first level(mt), reads A(mt+1) | element-wise(mt) || second level(mt-1) | reads B(mt)
+        bf16x8 qa[8], ga[8], gb[8], qb_[8], pa[2], ua[2];
         auto read_a = [&](int mt) {
             const int arow = mt * 32 + swap23(ql);
 #pragma unroll
             for (int ks = 0; ks < 8; ++ks) { qa[ks] = frag(q_img, arow, 2 * ks + half); ga[ks] = frag(g_img, arow, 2 * ks + half); }
         };
-        read_a(0);
-        for (int mt = 0; mt < n_units; ++mt) {
-            bf16x8 gb[8], qb_[8];                            // needed after the element-wise part: requested now
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                gb[i] = frag_down(g_img, mt * 32 + 16 * (i & 1), (i >> 1) * 32, lane);
-                qb_[i] = frag_down(q_img, mt * 32 + 16 * (i & 1), (i >> 1) * 32, lane);
-            }
-            __builtin_amdgcn_sched_barrier(0);               // keep the reads ahead of the products (the scheduler would sink each next to its use)
-            f32x16 s, dp;
-            zero(s); zero(dp);
-#pragma unroll
-            for (int ks = 0; ks < 8; ++ks) {
-                s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa[ks], kf[ks], s, 0, 0, 0);
-                dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ga[ks], vf[ks], dp, 0, 0, 0);
-            }
-            __builtin_amdgcn_sched_barrier(0);
-            if (mt + 1 < n_units) read_a(mt + 1);            // arrives under the element-wise part and the second-level products
-            __builtin_amdgcn_sched_barrier(0);
-            // lane = key ql of this wavefront; register 8 kk + j = query mt*32 + 16 kk + 8 half + j
-            bf16x8 pa[2], ua[2];
+        // lane = key ql of this wavefront; register 8 kk + j = query mt*32 + 16 kk + 8 half + j
+        auto element_wise = [&](int mt, const f32x16 &s, const f32x16 &dp, bf16x8 (&pn)[2], bf16x8 (&un)[2]) {
 #pragma unroll
             for (int kk = 0; kk < 2; ++kk) {
                 const int q0 = mt * 32 + 16 * kk + 8 * half;
@@ -510,10 +494,12 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
                     const int r = kk * 8 + j;
                     float p = __builtin_amdgcn_exp2f(fmaf(s[r], scale_log2, -l8[j]));
                     p = key_ok ? p : 0.f;
-                    pa[kk][j] = (__bf16)p;
-                    ua[kk][j] = (__bf16)(p * ((dp[r] - d8[j]) * scale));
+                    pn[kk][j] = (__bf16)p;
+                    un[kk][j] = (__bf16)(p * ((dp[r] - d8[j]) * scale));
                 }
             }
+        };
+        auto second_level = [&]() {
 #pragma unroll
             for (int nt = 0; nt < 4; ++nt)
 #pragma unroll
@@ -521,7 +507,42 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
                     dv[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pa[kk], gb[nt * 2 + kk], dv[nt], 0, 0, 0);
                     dk[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ua[kk], qb_[nt * 2 + kk], dk[nt], 0, 0, 0);
                 }
+        };
+        read_a(0);
+        for (int mt = 0; mt < n_units; ++mt) {
+            __builtin_amdgcn_sched_barrier(0);
+            f32x16 s, dp;
+            zero(s); zero(dp);
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks) {
+                s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa[ks], kf[ks], s, 0, 0, 0);
+                dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ga[ks], vf[ks], dp, 0, 0, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            if (mt + 1 < n_units) read_a(mt + 1);            // arrives under the element-wise part and the second-level products
+            __builtin_amdgcn_sched_barrier(0);
+            bf16x8 pn[2], un[2];
+            if (mt > 0) {
+                element_wise(mt, s, dp, pn, un);
+                second_level();
+#pragma unroll
+                for (int n = 0; n < 16; ++n) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x002, 8, 0);
+                }
+            } else {
+                element_wise(mt, s, dp, pn, un);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                gb[i] = frag_down(g_img, mt * 32 + 16 * (i & 1), (i >> 1) * 32, lane);
+                qb_[i] = frag_down(q_img, mt * 32 + 16 * (i & 1), (i >> 1) * 32, lane);
+            }
+            pa[0] = pn[0]; pa[1] = pn[1]; ua[0] = un[0]; ua[1] = un[1];
         }
+        __builtin_amdgcn_sched_barrier(0);
+        second_level();                                      // of the block's last unit
         buf ^= 1;
     }
     // tile nt: lane = channel nt*32 + ql, register r = key row 8 (r >> 2) + 4 half + (r & 3) of this wavefront
