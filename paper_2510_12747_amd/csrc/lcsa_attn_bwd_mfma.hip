@@ -129,14 +129,16 @@ __device__ inline RowPlan<WAVES> plan_rows(const KGeom &g, int vh, int vw, int w
 // One copy instruction: 64 lanes x 16 bytes from per-lane addresses to LDS bytes lds_rows + 16 lane.  The load
 // stays in flight (counted by vmcnt) until waited for; nothing else orders it.
 __device__ inline void copy_rows_to_lds(const void *src, uint32_t lds_rows) {
+    lds_rows = __builtin_amdgcn_readfirstlane(lds_rows);     // wavefront-uniform already; this pins it to a scalar register
     asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" :: "v"(src), "s"(lds_rows) : "memory", "m0");
 }
-// Copies this wavefront's rows (128 / WAVES of them) of the tiles of block `b` of two tensors that share strides
-// (K and V, or Q and dO).
+// Copies this wavefront's rows (128 / WAVES of them) of the tiles of block `b` of two tensors (K and V, or Q and dO);
+// x1 = the second tensor moved so that the first tensor's strides reach its elements too when the two share
+// strides (`same`, the usual case: one address computation serves both), else its own base with strides st1, sh1.
 template <int WAVES>
 __device__ inline void copy_tiles(const KGeom &g, const BlockRef &b, const RowPlan<WAVES> &full, int wave, int lane,
                                   const __bf16 *__restrict__ x0, const __bf16 *__restrict__ x1, int64_t st, int64_t sh, int head,
-                                  uint32_t lds0, uint32_t lds1) {
+                                  uint32_t lds0, uint32_t lds1, bool same = true, int64_t st1 = 0, int64_t sh1 = 0) {
     RowPlan<WAVES> plan = full;
     if (b.vh != g.th || b.vw != g.tw) plan = plan_rows<WAVES>(g, b.vh, b.vw, wave, lane);     // workgroup-uniform
     const int64_t origin = block_origin(g, b);
@@ -146,9 +148,10 @@ __device__ inline void copy_tiles(const KGeom &g, const BlockRef &b, const RowPl
     for (int i = 0; i < 32 / WAVES; ++i) {
         const int chunk = slot ^ sw(4 * i + q4);
         const int64_t at = ((origin + plan.rel[i]) * st + (int64_t)head * sh + chunk * 8) * 2;
+        const int64_t at1 = same ? at : ((origin + plan.rel[i]) * st1 + (int64_t)head * sh1 + chunk * 8) * 2;      // `same` is workgroup-uniform
         const bool ok = plan.rel[i] >= 0;
         const void *s0 = ok ? (const void *)((const char *)x0 + at) : (const void *)(zero_row + chunk * 16);
-        const void *s1 = ok ? (const void *)((const char *)x1 + at) : (const void *)(zero_row + chunk * 16);
+        const void *s1 = ok ? (const void *)((const char *)x1 + at1) : (const void *)(zero_row + chunk * 16);
         const uint32_t rows = (uint32_t)(first + 4 * i) * 256;
         copy_rows_to_lds(s0, lds0 + rows);
         copy_rows_to_lds(s1, lds1 + rows);
@@ -406,6 +409,8 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
 }
 
 // ---------------------------------------------------------------------------------------------------------------
+// SAME_STRIDES: Q and dO share their strides (the usual case: one address computation per copied row serves both).
+template <bool SAME_STRIDES>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))) void bwd_dkv_mfma_kernel(
     KGeom g, int kv_groups, const __bf16 *__restrict__ q, int64_t q_st, int64_t q_sh,
     const __bf16 *__restrict__ k, const __bf16 *__restrict__ v, int64_t kv_st, int64_t kv_sh,
@@ -451,7 +456,8 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
     float l2_next = 0.f, D_next = 0.f;
     auto request = [&](int qb_, int buf) {                   // a query block's tiles, lse and D
         const BlockRef qr = block_ref(g, qb_);
-        copy_tiles<4>(g, qr, full, wave, lane, q, d_o, q_st, q_sh, head, lds_img + buf * 2 * kTileBytes, lds_img + (buf * 2 + 1) * kTileBytes);
+        copy_tiles<4>(g, qr, full, wave, lane, q, d_o, q_st, q_sh, head, lds_img + buf * 2 * kTileBytes, lds_img + (buf * 2 + 1) * kTileBytes,
+                      SAME_STRIDES, o_st, o_sh);
         if (tid < 128) {
             const bool ok = tid < qr.n_valid;
             const int64_t token = token_of(g, qr, ok ? tid : 0);
@@ -578,9 +584,14 @@ hipError_t launch_attn_bwd_mfma(const KGeom &g, int kv_groups, const void *q, in
                                                            kv_st, kv_sh, sel_idx, sel_cnt, (const __bf16 *)d_o, o_st, o_sh, lse, d_q, delta, scale, q_per_xcd);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
-    bwd_dkv_mfma_kernel<<<grid_k, kThreads, 0, stream>>>(g, kv_groups, (const __bf16 *)q, q_st, q_sh, (const __bf16 *)k, (const __bf16 *)v,
-                                                         kv_st, kv_sh, sel_idx, sel_cnt, (const __bf16 *)d_o, o_st, o_sh, lse, delta,
-                                                         d_k, d_v, scale, k_per_xcd);
+    if (q_st == o_st && q_sh == o_sh)
+        bwd_dkv_mfma_kernel<true><<<grid_k, kThreads, 0, stream>>>(g, kv_groups, (const __bf16 *)q, q_st, q_sh, (const __bf16 *)k, (const __bf16 *)v,
+                                                                   kv_st, kv_sh, sel_idx, sel_cnt, (const __bf16 *)d_o, o_st, o_sh, lse, delta,
+                                                                   d_k, d_v, scale, k_per_xcd);
+    else
+        bwd_dkv_mfma_kernel<false><<<grid_k, kThreads, 0, stream>>>(g, kv_groups, (const __bf16 *)q, q_st, q_sh, (const __bf16 *)k, (const __bf16 *)v,
+                                                                    kv_st, kv_sh, sel_idx, sel_cnt, (const __bf16 *)d_o, o_st, o_sh, lse, delta,
+                                                                    d_k, d_v, scale, k_per_xcd);
     return hipGetLastError();
 }
 

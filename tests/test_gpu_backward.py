@@ -28,7 +28,7 @@ BARS = {"float": (2e-5, 2e-6),        # float FMA kernels, f32 and bf16 data ali
         "matrix": (6e-3, 6e-4)}       # matrix-core kernels: p and u enter the second-level products rounded to bf16
 
 
-def run_backward(w, chunks=None, seed=0, **kw):
+def run_backward(w, chunks=None, seed=0, d_o_layout="thd", **kw):
     p = Pipeline(w, **kw)
     for _ in range(w.prime_chunks + 1 if chunks is None else chunks):
         q, qd = p.feed()
@@ -42,7 +42,7 @@ def run_backward(w, chunks=None, seed=0, **kw):
     d_o = rng.standard_normal(q.shape).astype(np.float32)
     if w.dtype == "bf16":
         d_o = wl.round_to_bf16(d_o)
-    Kd, Vd, gd = to_device(K, w.dtype), to_device(V, w.dtype), to_device(d_o, w.dtype)
+    Kd, Vd, gd = to_device(K, w.dtype), to_device(V, w.dtype), to_device(d_o, w.dtype, d_o_layout)
     # the selection the gradients are taken on is the library's; it must be the oracle's up to reported near-ties
     S = oracle.scores(oracle.pool(q, og, g.q_frames), oracle.pool(K, og, kvf))
     o_idx, o_cnt, o_gap = oracle.select(S, og, kvf)
@@ -104,6 +104,13 @@ def test_backward_clipped_blocks_and_partly_filled_cache():
     w = wl.with_overrides(wl.WORKLOADS["small"], name="bwd-edge", heads=2, grid_h=20, grid_w=40, radius=16, topk=6)
     run_backward(w, chunks=2)                                   # 4 of 6 frames visible
     run_backward(wl.with_overrides(w, tile_h=8, tile_w=8, grid_h=21, grid_w=37, topk=9), tile_t=2, seed=1)
+
+
+def test_backward_each_tensor_with_strides_of_its_own():
+    """q token-major, dO head-major, K and V token-major: every tensor of the call is addressed through its own strides
+    (on the matrix cores the key-side kernel has a build of its own for Q and dO that do not share theirs)."""
+    w = wl.with_overrides(wl.WORKLOADS["small"], name="bwd-strides", heads=2, grid_h=20, grid_w=40, radius=16, topk=6)
+    run_backward(w, d_o_layout="htd")
 
 
 def test_backward_generic_bf16_d64():
