@@ -31,8 +31,8 @@
 //   bwd_dkv_mfma_kernel   workgroup = (head, key block), wavefront w owns keys 32w..32w+31 (K and V fragments in
 //                         registers).  Walks the query blocks that kept this block (ascending), per query block
 //                         the Q and dO tiles: dV += P^T dO, dK += U^T Q.
-// All three are bound by the rate at which tiles reach LDS (64 KB per block pair and kernel, from L2) and by LDS
-// itself (every matrix instruction takes one 1 KB operand fragment from it).
+// Every matrix instruction takes one 1 KB operand fragment from LDS (the 64-bit transposing reads at less than half
+// the rate of the 128-bit row reads), and every kernel fetches 64 KB of tiles per block pair from L2.
 #include "lcsa_kernels.h"
 
 #include <type_traits>
